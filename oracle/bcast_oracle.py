@@ -1,0 +1,368 @@
+"""CPU oracle for the scatter + ring-allgather broadcast of P virtual ranks.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain reference that the
+GPU library is checked against.  It is imported by the tests, by the smoke
+check and by the benchmark's CPU-baseline leg, never by the product path, and
+it shares no code with the HIP sources.
+
+What it models (paper sections in brackets):
+
+* every rank views its n-byte buffer as P chunks of ``ceil(n / P)`` bytes laid
+  out in relative-rank order, the last ones short or empty        [Sec. IV, listing]
+* a binomial scatter from the root: in ``ceil(log2 P)`` levels every subtree
+  root hands the upper half of its chunk range to the rank ``mask`` above it
+                                                          [Sec. III-A, Figs. 1-2]
+* the native ("enclosed") ring allgather: P-1 steps, every rank sends one
+  chunk to its right neighbour and receives one from its left    [Sec. III-A, Fig. 3]
+* the tuned ("non-enclosed") ring: every rank derives a pair (step, flag) from
+  its relative rank and, for the last ``step - 1`` ring steps, only sends or
+  only receives                                          [Sec. IV, listing, Figs. 4-5]
+
+The ring is written as P little per-rank programs advanced in lock step: each
+rank decides from its own variables what it sends and what it expects, and the
+oracle then checks that every posted send meets a posted receive with the same
+extent before delivering it.  Nothing is blocked, fused or reordered.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against
+the paper's worked examples (P = 8 and P = 10), closed forms, the definition of
+broadcast, an independent ownership-set model and an asynchronous mailbox
+execution.  No function is "parity unpinned".
+"""
+
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+NATIVE = "native"
+TUNED = "tuned"
+
+RECV_ONLY = 1  # the listing's flag = 1
+SEND_ONLY = 0  # the listing's flag = 0
+
+Row = Tuple[int, int, int, int]  # (src rank, dst rank, byte offset, byte length)
+
+
+# --------------------------------------------------------------------------
+# rank and chunk arithmetic                                   [Sec. IV, listing]
+# --------------------------------------------------------------------------
+
+def relative_rank(rank: int, root: int, P: int) -> int:
+    """Distance of ``rank`` above ``root`` on the ring of P ranks."""
+    return rank - root if rank >= root else rank - root + P
+
+
+def absolute_rank(rel: int, root: int, P: int) -> int:
+    """Inverse of :func:`relative_rank`."""
+    return (rel + root) % P
+
+
+def scatter_size(n: int, P: int) -> int:
+    """Chunk size: n bytes divided over P ranks, rounded up."""
+    return (n + P - 1) // P
+
+
+def chunk_extent(c: int, n: int, P: int) -> Tuple[int, int]:
+    """(displacement, count) of the chunk with relative index ``c``.
+
+    The count is what is left of the message at that displacement, at most one
+    scatter size and never negative.
+    """
+    ss = scatter_size(n, P)
+    disp = c * ss
+    count = min(ss, n - disp)
+    if count < 0:
+        count = 0
+    return disp, count
+
+
+def ceil_pow2(P: int) -> int:
+    """2 ** ceil(log2 P), in integers."""
+    m = 1
+    while m < P:
+        m *= 2
+    return m
+
+
+def ceil_log2(P: int) -> int:
+    k = 0
+    while (1 << k) < P:
+        k += 1
+    return k
+
+
+# --------------------------------------------------------------------------
+# binomial scatter                                      [Sec. III-A, Figs. 1-2]
+# --------------------------------------------------------------------------
+
+def scatter_levels(P: int, root: int, n: int) -> List[List[Row]]:
+    """One list of messages per level of the binomial tree.
+
+    At the level with distance ``mask`` every relative rank that is a multiple
+    of ``2 * mask`` is a subtree root holding the chunks ``[rho, rho + 2*mask)``
+    (clipped to P); it keeps the lower half and sends the upper half, as one
+    contiguous message, to relative rank ``rho + mask`` if that rank exists.
+    Levels run from the largest distance down to 1, so the root's first
+    message is the one that spawns the largest subtree.  Empty messages are
+    not sent.
+    """
+    levels: List[List[Row]] = []
+    mask = ceil_pow2(P) // 2
+    while mask >= 1:
+        rows: List[Row] = []
+        for rho in range(0, P, 2 * mask):
+            child = rho + mask
+            if child >= P:
+                continue
+            upper_end = min(rho + 2 * mask, P)
+            disp, _ = chunk_extent(child, n, P)
+            length = sum(chunk_extent(c, n, P)[1] for c in range(child, upper_end))
+            if length > 0:
+                rows.append((absolute_rank(rho, root, P),
+                             absolute_rank(child, root, P), disp, length))
+        levels.append(rows)
+        mask //= 2
+    return levels
+
+
+def owned_after_scatter(rel: int, P: int) -> range:
+    """Relative chunk indices a rank holds once the scatter is over: its own
+    chunk and those of all its descendants in the tree."""
+    if rel == 0:
+        return range(0, P)
+    span = 1
+    while rel % (2 * span) == 0:
+        span *= 2
+    return range(rel, min(rel + span, P))
+
+
+# --------------------------------------------------------------------------
+# the tuned ring's per-rank switch point                      [Sec. IV, listing]
+# --------------------------------------------------------------------------
+
+def tuned_switch(rel: int, P: int) -> Optional[Tuple[int, int]]:
+    """(step, flag) of the rank with relative rank ``rel``.
+
+    Scanning distances from 2**ceil(log2 P) down to 2: if the right neighbour's
+    relative rank is a multiple of the distance, the neighbour heads a subtree
+    of ``step`` chunks and this rank ends up receive-only; otherwise, if the
+    rank's own relative rank is a multiple, the rank itself heads such a
+    subtree and ends up send-only.  ``step`` is the distance, clipped so the
+    subtree does not run past the last rank.  Returns None when no distance
+    qualifies (only for P = 1, where there is no ring).
+    """
+    mask = ceil_pow2(P)
+    while mask > 1:
+        right_rel = rel + 1 if rel + 1 < P else rel + 1 - P
+        if right_rel % mask == 0:
+            step = mask
+            if right_rel + mask > P:
+                step = P - right_rel
+            return step, RECV_ONLY
+        if rel % mask == 0:
+            step = mask
+            if rel + mask > P:
+                step = P - rel
+            return step, SEND_ONLY
+        mask >>= 1
+    return None
+
+
+# --------------------------------------------------------------------------
+# ring allgather, native and tuned          [Sec. III-A Fig. 3; Sec. IV listing]
+# --------------------------------------------------------------------------
+
+@dataclass
+class RingResult:
+    steps: List[List[Row]]          # delivered messages with len > 0, per ring step
+    posted_sends: List[int]         # sends posted per step, zero-length ones included
+    posted_recvs: List[int]         # receives posted per step
+
+
+def ring_steps(P: int, root: int, n: int, algo: str) -> RingResult:
+    """Advance P per-rank programs through the P-1 ring steps.
+
+    Every rank keeps the cursor (j, jnext): the owner of the chunk it sends
+    next and the owner of the chunk it receives next.  It starts with its own
+    chunk and its left neighbour's, and after every step both move one rank to
+    the left, so a rank always forwards what it received one step earlier.
+
+    native: every rank sends and receives in every step.
+    tuned : a rank does both while ``step <= P - i``; afterwards it only
+            receives (flag = 1) or only sends (flag = 0).
+    """
+    if algo not in (NATIVE, TUNED):
+        raise ValueError(algo)
+    order = [absolute_rank(rho, root, P) for rho in range(P)]  # by relative rank
+    cursor = {r: (r, (P + r - 1) % P) for r in range(P)}
+    switch = {r: tuned_switch(relative_rank(r, root, P), P) for r in range(P)}
+
+    out = RingResult([], [], [])
+    for i in range(1, P):
+        sends = {}   # (src, dst) -> (disp, count), posted by the sender
+        recvs = {}   # (src, dst) -> (disp, count), posted by the receiver
+        for r in order:
+            left = (P + r - 1) % P
+            right = (r + 1) % P
+            j, jnext = cursor[r]
+            right_disp, right_count = chunk_extent(relative_rank(j, root, P), n, P)
+            left_disp, left_count = chunk_extent(relative_rank(jnext, root, P), n, P)
+
+            if algo == NATIVE:
+                do_send = do_recv = True
+            else:
+                step, flag = switch[r]
+                if step <= P - i:
+                    do_send = do_recv = True
+                elif flag == RECV_ONLY:
+                    do_send, do_recv = False, True
+                else:
+                    do_send, do_recv = True, False
+
+            if do_send:
+                sends[(r, right)] = (right_disp, right_count)
+            if do_recv:
+                recvs[(left, r)] = (left_disp, left_count)
+            cursor[r] = (jnext, (P + jnext - 1) % P)
+
+        # Blocking point-to-point calls complete only in matched pairs.
+        if sends != recvs:
+            raise AssertionError(
+                f"ring step {i}: posted sends and receives do not pair up "
+                f"(P={P}, root={root}, n={n}, algo={algo})")
+        out.posted_sends.append(len(sends))
+        out.posted_recvs.append(len(recvs))
+        rows = [(src, dst, disp, cnt)
+                for (src, dst), (disp, cnt) in sends.items() if cnt > 0]
+        out.steps.append(rows)
+    return out
+
+
+# --------------------------------------------------------------------------
+# the whole schedule
+# --------------------------------------------------------------------------
+
+@dataclass
+class Schedule:
+    P: int
+    root: int
+    n: int
+    algo: str
+    ss: int
+    n_scatter_steps: int
+    steps: List[List[Row]] = field(default_factory=list)  # scatter levels, then ring steps
+    ring_msgs_issued: int = 0   # ring sends posted, zero-length ones included
+
+    @property
+    def n_steps(self) -> int:
+        return len(self.steps)
+
+    def step_bytes(self) -> List[int]:
+        return [sum(r[3] for r in rows) for rows in self.steps]
+
+    def step_rows(self) -> List[int]:
+        return [len(rows) for rows in self.steps]
+
+    @property
+    def scatter_bytes(self) -> int:
+        return sum(self.step_bytes()[: self.n_scatter_steps])
+
+    @property
+    def ring_bytes(self) -> int:
+        return sum(self.step_bytes()[self.n_scatter_steps:])
+
+    @property
+    def bytes_moved(self) -> int:
+        return sum(self.step_bytes())
+
+    @property
+    def ring_rows(self) -> int:
+        return sum(self.step_rows()[self.n_scatter_steps:])
+
+
+def build_schedule(P: int, root: int, n: int, algo: str) -> Schedule:
+    """Scatter levels followed by ring steps; one level or ring step = one step.
+
+    Rows inside a step are ordered by the sender's relative rank.
+    """
+    if P < 1 or not (0 <= root < P) or n < 0:
+        raise ValueError("bad (P, root, n)")
+    levels = scatter_levels(P, root, n)
+    ring = ring_steps(P, root, n, algo)
+    return Schedule(P=P, root=root, n=n, algo=algo, ss=scatter_size(n, P),
+                    n_scatter_steps=len(levels),
+                    steps=levels + ring.steps,
+                    ring_msgs_issued=sum(ring.posted_sends))
+
+
+# --------------------------------------------------------------------------
+# executing a schedule on byte buffers
+# --------------------------------------------------------------------------
+
+def apply_step(bufs: Sequence[np.ndarray], rows: Sequence[Row]) -> None:
+    """Deliver all messages of one step.
+
+    All sends of a step read the state from before the step: payloads are
+    taken first, then written at the same offset in the receiver's buffer.
+    """
+    payloads = [bufs[src][off:off + length].copy() for (src, _dst, off, length) in rows]
+    for (_src, dst, off, length), data in zip(rows, payloads):
+        bufs[dst][off:off + length] = data
+
+
+def run_steps(bufs: Sequence[np.ndarray], sched: Schedule,
+              first: int = 0, last: Optional[int] = None) -> None:
+    """Apply steps ``[first, last)`` of the schedule, in order."""
+    if last is None:
+        last = sched.n_steps
+    for s in range(first, last):
+        apply_step(bufs, sched.steps[s])
+
+
+def broadcast_definition(bufs: Sequence[np.ndarray], root: int, n: int) -> List[np.ndarray]:
+    """What MPI requires of any broadcast: on return the first n bytes of every
+    rank's buffer equal the root's; nothing else changes.       [Sec. III-A]"""
+    out = [b.copy() for b in bufs]
+    for b in out:
+        b[:n] = bufs[root][:n]
+    return out
+
+
+# --------------------------------------------------------------------------
+# chunk-ownership form of the state (no byte buffers needed)
+# --------------------------------------------------------------------------
+
+def ownership_after(sched: Schedule, k: int) -> np.ndarray:
+    """has[rank, c] after the first k steps: does ``rank`` hold valid (root's)
+    data in the chunk with relative index ``c``?
+
+    Every message moves whole chunks at unchanged offsets, so the byte state
+    is: root's bytes where has[...] is set, the rank's initial bytes elsewhere.
+    A message that would carry a chunk its sender does not hold is an error.
+    """
+    P, root, n = sched.P, sched.root, sched.n
+    has = np.zeros((P, P), dtype=bool)
+    has[root, :] = True
+    ss = scatter_size(n, P)
+    for s in range(k):
+        before = has.copy()
+        for (src, dst, off, length) in sched.steps[s]:
+            # walk the chunks the message covers, starting at the one at `off`
+            c = off // ss
+            covered = []
+            remaining = length
+            while remaining > 0:
+                disp, cnt = chunk_extent(c, n, P)
+                if cnt == 0 or cnt > remaining or (not covered and disp != off):
+                    raise AssertionError("message does not consist of whole chunks")
+                covered.append(c)
+                remaining -= cnt
+                c += 1
+            for c in covered:
+                if not before[src, c]:
+                    raise AssertionError(
+                        f"step {s}: rank {src} sends chunk {c} it does not hold")
+                has[dst, c] = True
+    return has

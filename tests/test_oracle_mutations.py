@@ -1,0 +1,114 @@
+"""Are the pins sharp?  Plant one plausible mistake at a time in a copy of the
+oracle's source and check that the pin suite rejects every one of them.  The
+mistakes are planted in the oracle, on the CPU; nothing here touches a GPU."""
+
+import os
+import sys
+import types
+
+import pytest
+
+import test_oracle_pins as pins
+import test_oracle_mailbox as mailbox
+
+SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                   "oracle", "bcast_oracle.py")
+
+MUTANTS = {
+    "chunk size rounded down": (
+        "return (n + P - 1) // P", "return max(1, n // P)"),
+    "negative chunk count not clamped": (
+        "    if count < 0:\n        count = 0\n", ""),
+    "relative rank measured the wrong way round": (
+        "return rank - root if rank >= root else rank - root + P",
+        "return root - rank if root >= rank else root - rank + P"),
+    "scatter hands over the lower half": (
+        "disp, _ = chunk_extent(child, n, P)\n            length = sum(chunk_extent(c, n, P)[1] for c in range(child, upper_end))",
+        "disp, _ = chunk_extent(rho, n, P)\n            length = sum(chunk_extent(c, n, P)[1] for c in range(rho, child))"),
+    "scatter levels smallest distance first": (
+        "    mask = ceil_pow2(P) // 2\n    while mask >= 1:\n        rows: List[Row] = []",
+        "    for mask in [1 << k for k in range(ceil_log2(P))]:\n        rows: List[Row] = []"),
+    "switch: own subtree tested before the neighbour's": (
+        "        if right_rel % mask == 0:\n            step = mask\n            if right_rel + mask > P:\n                step = P - right_rel\n            return step, RECV_ONLY\n",
+        ""),
+    "switch: subtree size not clipped": (
+        "            if rel + mask > P:\n                step = P - rel\n", ""),
+    "switch: directions swapped": (
+        "            return step, SEND_ONLY", "            return step, RECV_ONLY"),
+    "switch: scan stops before distance 2": (
+        "    while mask > 1:\n        right_rel", "    while mask > 2:\n        right_rel"),
+    "ring: one-direction phase starts a step late": (
+        "if step <= P - i:", "if step <= P - i + 1:"),
+    "ring: one-direction phase starts a step early": (
+        "if step <= P - i:", "if step < P - i:"),
+    "ring: cursor walks to the right": (
+        "cursor[r] = (jnext, (P + jnext - 1) % P)", "cursor[r] = (jnext, (jnext + 1) % P)"),
+    "ring: first chunk sent is the left neighbour's": (
+        "cursor = {r: (r, (P + r - 1) % P) for r in range(P)}",
+        "cursor = {r: ((P + r - 1) % P, (P + r - 2) % P) for r in range(P)}"),
+    "ring: chunk looked up by absolute rank": (
+        "right_disp, right_count = chunk_extent(relative_rank(j, root, P), n, P)",
+        "right_disp, right_count = chunk_extent(j, n, P)"),
+    "ring: sends go to the left neighbour": (
+        "sends[(r, right)] = (right_disp, right_count)", "sends[(r, left)] = (right_disp, right_count)"),
+    "delivery lands at the wrong offset": (
+        "bufs[dst][off:off + length] = data", "bufs[dst][off - length:off] = data[:len(bufs[dst][off - length:off])]"),
+    "delivery reads the receiver's buffer": (
+        "payloads = [bufs[src][off:off + length].copy() for (src, _dst, off, length) in rows]",
+        "payloads = [bufs[_dst][off:off + length].copy() for (src, _dst, off, length) in rows]"),
+    "zero-length rows kept": (
+        "for (src, dst), (disp, cnt) in sends.items() if cnt > 0]",
+        "for (src, dst), (disp, cnt) in sends.items()]"),
+}
+
+
+def load_mutant(old, new):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, "mutation site not found - keep this test in step with the oracle"
+    mod = types.ModuleType("bcast_oracle_mutant")
+    mod.__file__ = SRC
+    sys.modules[mod.__name__] = mod      # dataclasses look their module up by name
+    exec(compile(text.replace(old, new), SRC, "exec"), mod.__dict__)
+    return mod
+
+
+def run_pin_suite():
+    """A compact pass over the pin tests (same functions pytest collects)."""
+    pins.test_chunking()
+    pins.test_switch_point_values()
+    pins.test_scatter_tree_8_processes()
+    pins.test_scatter_tree_10_processes()
+    for P in (5, 6, 10, 12):
+        pins.test_scatter_matches_recursive_halving(P)
+    for case in [(10, 3, 1000), (10, 0, 12), (7, 2, 5)]:
+        pins.test_state_after_scatter_is_own_subtree_only(*case)
+    pins.test_native_ring_forwards_what_arrived(10, 7)
+    pins.test_native_ring_count_paper_examples()
+    pins.test_tuned_ring_8_processes_narrative()
+    pins.test_tuned_ring_10_processes_narrative()
+    pins.test_tuned_saving_power_of_two(4)
+    for P in (6, 9, 10, 16):
+        pins.test_tuned_rule_equals_only_missing_chunks(P)
+    for case in [(10, 9, 9), (10, 3, 32), (13, 4, 14), (5, 0, 1000)]:
+        pins.test_final_state_is_the_broadcast(*case)
+    pins.test_tuned_writes_every_missing_byte_exactly_once(10, 4, 1003)
+    pins.test_byte_counts_closed_form(10, 0, 12)
+    pins.test_byte_counts_closed_form(33, 7, 20)
+    pins.test_degenerate_cases()
+    mailbox.test_async_execution_agrees_with_the_tables(10, 5, 32)
+    mailbox.test_async_execution_agrees_with_the_tables(9, 8, 10)
+
+
+def test_unmutated_oracle_passes_the_compact_suite():
+    run_pin_suite()
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_reject_mutant(name, monkeypatch):
+    old, new = MUTANTS[name]
+    mutant = load_mutant(old, new)
+    monkeypatch.setattr(pins, "O", mutant)
+    monkeypatch.setattr(mailbox, "O", mutant)
+    with pytest.raises(BaseException) as info:
+        run_pin_suite()
+    assert not isinstance(info.value, (KeyboardInterrupt, SystemExit))
