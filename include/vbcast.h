@@ -1,0 +1,206 @@
+/*
+ * vbcast - the large-message MPI broadcast (binomial scatter followed by a ring
+ * allgather) of P virtual ranks whose buffers all live in one GPU's memory.
+ *
+ * The library follows MPI_Bcast(buffer, count, datatype, root, comm) as the
+ * paper's MPI_Bcast_native / MPI_Bcast_opt use it [Sec. I; Sec. IV, listing]:
+ *   - comm      -> a virtual communicator: P device buffers, one per rank;
+ *   - buffer    -> implicit, rank r broadcasts into / out of its own buffer;
+ *   - datatype  -> its size in bytes; the message is n = count * dtype_size bytes
+ *                  of opaque data (the paper sends MPI_BYTE);
+ *   - root      -> absolute rank whose buffer holds the message on entry.
+ * After bcast_run has completed on its stream, the first n bytes of every
+ * rank's buffer equal the root's [Sec. III-A]; bytes at offsets >= n are never
+ * touched.
+ *
+ * Two schedules are provided [Sec. III-A and Sec. IV]:
+ *   VBCAST_NATIVE  scatter + "enclosed" ring: every rank sends and receives one
+ *                  chunk in each of the P-1 ring steps;
+ *   VBCAST_TUNED   scatter + "non-enclosed" ring: a rank stops receiving once it
+ *                  holds the whole message and its left neighbour stops sending
+ *                  to it; same number of steps, fewer bytes.
+ *
+ * A schedule is a list of steps: ceil(log2 P) scatter levels, then P-1 ring
+ * steps.  A step is a table of rows (src rank, dst rank, byte offset, byte
+ * length), ordered by the sender's rank relative to the root; a row means
+ * "copy length bytes at that offset from src's buffer to the same offset in
+ * dst's buffer".  Rows with length 0 are not stored.  All rows of a step are
+ * independent; steps must run in order.  Tables are generated on the GPU.
+ *
+ * Conventions
+ *   - All functions return 0 (VBCAST_SUCCESS) or a VBCAST_ERR_* code; nothing
+ *     is thrown or printed.  bcast_strerror() gives a text; for VBCAST_ERR_HIP
+ *     it includes the HIP runtime's own message for the calling thread's last
+ *     failure.
+ *   - "host pointer" / "device pointer" is stated per argument.  Streams are
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Argument checks happen before any GPU call, so invalid arguments are
+ *     rejected without touching a device.
+ *   - The library owns what it creates (communicator, plan, tables, graph) and
+ *     nothing else: it never allocates, frees or initialises a rank buffer.
+ *   - Not thread-safe per object: do not use one communicator or plan from two
+ *     threads at once.  Two runs that overlap in time on the same rank buffers
+ *     race.
+ */
+#ifndef VBCAST_H
+#define VBCAST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vbcast_comm vbcast_comm; /* P virtual ranks = P device buffers */
+typedef struct vbcast_plan vbcast_plan; /* tables, tile maps, instantiated graph */
+
+enum { VBCAST_NATIVE = 0, VBCAST_TUNED = 1 };
+
+enum {
+    VBCAST_SUCCESS = 0,
+    VBCAST_ERR_ARG = 1,   /* null pointer, P < 1, bad algo, bad step range, bad option */
+    VBCAST_ERR_ROOT = 2,  /* root outside [0, P) */
+    VBCAST_ERR_COUNT = 3, /* count * dtype_size overflows or exceeds the rank buffers */
+    VBCAST_ERR_ALIGN = 4, /* a rank buffer is not 16-byte aligned */
+    VBCAST_ERR_HIP = 5,   /* a HIP runtime call failed */
+    VBCAST_ERR_NOMEM = 6  /* host or device allocation failed */
+};
+
+/* Largest communicator accepted (tables grow with P * P). */
+#define VBCAST_MAX_RANKS 8192
+
+/*
+ * Create a communicator of P ranks [Sec. III-A: "P processes participating"].
+ *   rank_bufs  host array of P device pointers; rank r's buffer.  Every pointer
+ *              must be 16-byte aligned so that a copy at equal offsets in two
+ *              buffers is equally aligned on both sides.  Buffers must not
+ *              overlap (not checked).  The array is copied; the buffers stay
+ *              the caller's and must outlive the communicator's use.
+ *   buf_bytes  usable size of every rank buffer.
+ *   out        host pointer receiving the handle.
+ * Errors: ARG (P < 1, P > VBCAST_MAX_RANKS, null), ALIGN, HIP, NOMEM.
+ */
+int vbcast_comm_create(int P, void *const *rank_bufs, size_t buf_bytes, vbcast_comm **out);
+
+/* Destroy a communicator.  Plans made from it must be destroyed first. */
+int vbcast_comm_destroy(vbcast_comm *comm);
+
+/*
+ * Generate the schedule of one broadcast on the GPU [Sec. IV, listing]:
+ * chunk size ceil(n / P) and chunk extents in relative-rank order, every rank's
+ * relative rank, ring neighbours and tuned switch point (step, flag), the
+ * scatter-level tables [Sec. III-A, Figs. 1-2], the ring-step tables
+ * [Sec. III-A Fig. 3 for NATIVE; Sec. IV Figs. 4-5 for TUNED], and for every
+ * step the map from copy tiles to rows.  Then record one graph that holds the
+ * table-generation kernels followed by one copy kernel per step.
+ *   comm        communicator; must outlive the plan.
+ *   count, dtype_size   message = count * dtype_size bytes; 0 is valid.
+ *   root        absolute rank in [0, P).
+ *   algo        VBCAST_NATIVE or VBCAST_TUNED.
+ *   hip_stream  stream the generation kernels run on; the call synchronises
+ *               this stream before it returns (it reads per-step counts back).
+ *   out         host pointer receiving the handle.
+ * Errors: ARG, ROOT, COUNT, HIP, NOMEM.  P = 1 and n = 0 give valid plans that
+ * move nothing.
+ */
+int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int root, int algo,
+               void *hip_stream, vbcast_plan **out);
+
+/*
+ * Run the whole broadcast [Sec. IV, listing: scatter, then ring]: launches the
+ * plan's graph on hip_stream and returns without waiting (MPI's "blocking" is
+ * the caller's stream synchronisation).  Every launch regenerates the tables
+ * on the device and then executes all steps in order.
+ * Errors: ARG (null), HIP.
+ */
+int bcast_run(const vbcast_plan *plan, void *hip_stream);
+
+/*
+ * Run steps [first, last) only, as plain kernel launches on hip_stream (no
+ * graph, tables as they are in device memory), asynchronously.  Used to look at
+ * the state between steps.  Steps count scatter levels first, then ring steps.
+ * Errors: ARG (null, first < 0, first > last, last > n_steps), HIP.
+ */
+int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stream);
+
+/*
+ * As bcast_run_steps, but brackets every step's kernel with events recorded on
+ * hip_stream, waits for the last one and writes the elapsed milliseconds of
+ * step first + i to step_ms[i] (host array of last - first floats; 0 for a step
+ * that moves nothing).  Synchronous.
+ */
+int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hip_stream,
+                          float *step_ms);
+
+typedef struct vbcast_plan_info {
+    int32_t P, root, algo;
+    int32_t n_scatter_steps; /* ceil(log2 P) */
+    int32_t n_steps;         /* n_scatter_steps + P - 1; 0 for P = 1 */
+    int32_t tile_bytes;      /* copy tile size the plan was built for */
+    uint64_t n;              /* message bytes */
+    uint64_t ss;             /* chunk size ceil(n / P) */
+    uint64_t scatter_rows, ring_rows;   /* stored rows (length > 0) */
+    uint64_t scatter_bytes, ring_bytes; /* bytes moved, one direction */
+    uint64_t bytes_moved;               /* scatter_bytes + ring_bytes */
+    uint64_t ring_msgs_issued; /* ring sends the ranks post, zero-length ones included
+                                  [Sec. III-A: P (P - 1) native; Sec. IV: fewer tuned] */
+    uint64_t pairing_mismatches; /* ring (step, rank) pairs where the sender's and the
+                                    receiver's own decisions disagree; always 0 */
+    uint64_t n_tiles;            /* copy tiles over all steps */
+} vbcast_plan_info;
+
+/* Fill *info (host pointer) from the counts read back at plan time. */
+int bcast_plan_info(const vbcast_plan *plan, vbcast_plan_info *info);
+
+/*
+ * Copy the step tables to the host (synchronous).  Any output may be NULL.
+ *   step_ptr    n_steps + 1 entries; rows of step s are [step_ptr[s], step_ptr[s+1])
+ *   src, dst    one entry per row: absolute ranks
+ *   off, len    one entry per row: byte offset and length
+ *   step_bytes  n_steps entries: bytes moved by the step
+ * Row arrays need room for scatter_rows + ring_rows entries.
+ */
+int bcast_plan_export(const vbcast_plan *plan, uint64_t *step_ptr, uint32_t *src, uint32_t *dst,
+                      uint64_t *off, uint64_t *len, uint64_t *step_bytes);
+
+/*
+ * Copy the chunk and rank descriptors to the host (synchronous); any output may
+ * be NULL [Sec. IV, listing].
+ *   chunk_off  P + 1 entries: running sum of the chunk lengths (entry P = n)
+ *   chunk_len  P entries: clamp(n - c * ss, 0, ss) for relative chunk index c
+ *   rel, left, right   P entries each, by absolute rank: relative rank and ring
+ *                      neighbours
+ *   sw_step, sw_flag   P entries each, by absolute rank: the tuned ring's switch
+ *                      point; flag 1 = receive-only tail, 0 = send-only tail;
+ *                      both -1 when P = 1
+ */
+int bcast_plan_export_desc(const vbcast_plan *plan, uint64_t *chunk_off, uint64_t *chunk_len,
+                           int32_t *rel, int32_t *left, int32_t *right, int32_t *sw_step,
+                           int32_t *sw_flag);
+
+/*
+ * Copy one step's tile map to the host (synchronous): tile t of the step copies
+ * the part of row tile_row[t] that lies in the tile_idx[t]-th tile_bytes-aligned
+ * window the row touches.  Arrays need *n_tiles entries; call with NULL arrays to
+ * get the count first.
+ */
+int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles,
+                            uint32_t *tile_row, uint32_t *tile_idx);
+
+int bcast_plan_destroy(vbcast_plan *plan);
+
+/*
+ * Copy-tile size used by plans created afterwards: a power of two between 4096
+ * and 65536 bytes.  Process-wide; returns ARG for other values.
+ */
+int vbcast_set_tile_bytes(size_t tile_bytes);
+
+/* Text for an error code; never NULL.  The pointer is valid until the calling
+ * thread's next library call. */
+const char *bcast_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VBCAST_H */

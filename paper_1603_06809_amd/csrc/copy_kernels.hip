@@ -1,0 +1,97 @@
+// Step execution: one launch moves every row of one step.
+//
+// A row copies `len` bytes at offset `off` from one rank buffer to the same
+// offset in another [Sec. IV, listing: the send and the matching receive use
+// the same displacement].  Rank buffers are 16-byte aligned, so source and
+// destination of a row are always equally aligned and the copy can use 16-byte
+// accesses throughout, with at most 15 single bytes at either end of a row.
+//
+// Rows are cut at multiples of the tile size measured from the start of the
+// buffer, so every tile except a row's first and last is a whole, aligned
+// window; one workgroup of 256 lanes copies one tile.  Consecutive lanes touch
+// consecutive 16-byte words (one wavefront = 1 KiB contiguous per access), and
+// a lane issues all its loads before its first store.
+
+#include "vbcast_internal.h"
+
+namespace vbcast {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int TILE_LOG2>
+__global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ rows,
+                                                      const Tile *__restrict__ tiles,
+                                                      uint8_t *const *__restrict__ bases) {
+    constexpr uint64_t TILE = 1ull << TILE_LOG2;
+    constexpr int WORDS = (int)(TILE / 16);      // 16-byte words in a full tile
+    constexpr int PER_LANE = WORDS / kThreads;   // words per lane in a full tile
+    static_assert(PER_LANE >= 1, "tile too small for the workgroup");
+
+    const Tile t = tiles[blockIdx.x];
+    const Row r = rows[t.row];
+    const uint8_t *__restrict__ src = bases[r.src];
+    uint8_t *__restrict__ dst = bases[r.dst];
+
+    const uint64_t window = ((r.off >> TILE_LOG2) + t.idx) << TILE_LOG2;
+    const uint64_t end = r.off + r.len;
+    const uint64_t lo = window > r.off ? window : r.off;
+    const uint64_t hi = window + TILE < end ? window + TILE : end;
+
+    const uint32_t tid = threadIdx.x;
+
+    if (hi - lo == TILE) {  // whole aligned window
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src + lo);
+        u32x4 *d = reinterpret_cast<u32x4 *>(dst + lo);
+        u32x4 v[PER_LANE];
+#pragma unroll
+        for (int k = 0; k < PER_LANE; ++k) v[k] = s[tid + k * kThreads];
+#pragma unroll
+        for (int k = 0; k < PER_LANE; ++k) d[tid + k * kThreads] = v[k];
+        return;
+    }
+
+    // Ragged tile: bytes up to the next 16-byte boundary, 16-byte words, bytes
+    // after the last boundary.
+    uint64_t body = (lo + 15) & ~15ull;
+    if (body > hi) body = hi;
+    uint64_t tail = hi & ~15ull;
+    if (tail < body) tail = body;
+
+    if (tid < (uint32_t)(body - lo)) dst[lo + tid] = src[lo + tid];
+    if (tid >= 64 && tid - 64 < (uint32_t)(hi - tail)) dst[tail + tid - 64] = src[tail + tid - 64];
+
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(src + body);
+    u32x4 *d = reinterpret_cast<u32x4 *>(dst + body);
+    const uint32_t words = (uint32_t)((tail - body) >> 4);
+    uint32_t w = tid;
+    for (; w + 3 * kThreads < words; w += 4 * kThreads) {
+        const u32x4 a = s[w], b = s[w + kThreads], c = s[w + 2 * kThreads], e = s[w + 3 * kThreads];
+        d[w] = a;
+        d[w + kThreads] = b;
+        d[w + 2 * kThreads] = c;
+        d[w + 3 * kThreads] = e;
+    }
+    for (; w < words; w += kThreads) d[w] = s[w];
+}
+
+}  // namespace
+
+hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
+                            uint32_t n_tiles, int tile_log2, hipStream_t stream) {
+    const dim3 grid(n_tiles), block(kThreads);
+    switch (tile_log2) {
+        case 12: hipLaunchKernelGGL(step_copy<12>, grid, block, 0, stream, rows, tiles, bases); break;
+        case 13: hipLaunchKernelGGL(step_copy<13>, grid, block, 0, stream, rows, tiles, bases); break;
+        case 14: hipLaunchKernelGGL(step_copy<14>, grid, block, 0, stream, rows, tiles, bases); break;
+        case 15: hipLaunchKernelGGL(step_copy<15>, grid, block, 0, stream, rows, tiles, bases); break;
+        case 16: hipLaunchKernelGGL(step_copy<16>, grid, block, 0, stream, rows, tiles, bases); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace vbcast

@@ -1,0 +1,295 @@
+// Schedule generation on the GPU: chunk and rank descriptors, per-step row
+// tables of the binomial scatter and of the native / tuned ring allgather, and
+// the tile maps the copy kernel is launched over.
+//
+// Layout of the work: one workgroup of 4 wavefronts (64 lanes each) per step,
+// lanes over the senders' relative ranks in ascending order.  Rows that exist
+// are compacted with a wavefront ballot (index inside the wave = number of set
+// bits below the lane) and an LDS exchange of the per-wave totals; the tiles
+// per row are turned into an exclusive prefix sum the same way.
+
+#include "vbcast_internal.h"
+
+namespace vbcast {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ uint32_t lane() { return __lane_id(); }
+
+template <class T>
+__device__ __forceinline__ T wave_inclusive_scan(T v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        T o = __shfl_up(v, d, 64);
+        if ((int)lane() >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan over the workgroup in thread order; returns this thread's
+// prefix and the workgroup total.  `slots` is LDS for kWaves values.
+template <class T>
+__device__ __forceinline__ T block_exclusive_scan(T v, T *slots, T &total) {
+    const int w = threadIdx.x >> 6;
+    T incl = wave_inclusive_scan(v);
+    if (lane() == 63) slots[w] = incl;
+    __syncthreads();
+    T before = 0, all = 0;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        T t = slots[k];
+        if (k < w) before += t;
+        all += t;
+    }
+    __syncthreads();
+    total = all;
+    return before + incl - v;
+}
+
+// Same for a predicate: the prefix comes from a ballot instead of a scan.
+__device__ __forceinline__ uint32_t block_exclusive_count(bool pred, uint32_t *slots,
+                                                          uint32_t &total) {
+    const int w = threadIdx.x >> 6;
+    const uint64_t votes = __ballot(pred);
+    const uint32_t below = __popcll(votes & ((1ull << lane()) - 1ull));
+    if (lane() == 0) slots[w] = __popcll(votes);
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        uint32_t t = slots[k];
+        if (k < w) before += t;
+        all += t;
+    }
+    __syncthreads();
+    total = all;
+    return before + below;
+}
+
+__device__ __forceinline__ uint32_t lowbit(uint32_t x) { return x & (0u - x); }
+
+// ---------------------------------------------------------------------------
+// Kernel 1: descriptors.  One workgroup.
+//
+// Chunk c (relative index) has length clamp(n - c * ss, 0, ss); its offset is
+// the running sum of the lengths before it [Sec. IV, listing: counts and
+// displacements].  Rank r has relative rank (r - root) mod P, ring neighbours
+// r -+ 1 mod P, and the tuned ring's switch point (step, flag) [Sec. IV,
+// listing: the scan over halving distances].  That scan stops at the largest
+// power of two dividing the right neighbour's relative rank (receive-only
+// tail) or, failing that, the rank's own (send-only tail); a relative rank of
+// 0 is divisible by every distance, so the root and its left neighbour stop at
+// the very first distance with step = P.  Lowest-set-bit arithmetic gives the
+// same result without a loop.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void plan_descriptors(PlanArrays pa) {
+    __shared__ uint64_t slots[kWaves];
+    const int P = pa.P;
+    uint64_t carry = 0;
+    for (int base = 0; base < P; base += kThreads) {
+        const int c = base + (int)threadIdx.x;
+        uint64_t len = 0;
+        if (c < P) {
+            const uint64_t disp = (uint64_t)c * pa.ss;
+            if (disp < pa.n) len = (pa.n - disp < pa.ss) ? pa.n - disp : pa.ss;
+        }
+        uint64_t total;
+        const uint64_t before = block_exclusive_scan<uint64_t>(len, slots, total);
+        if (c < P) {
+            pa.chunk_len[c] = len;
+            pa.chunk_off[c] = carry + before;
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) pa.chunk_off[P] = carry;
+
+    for (int r = threadIdx.x; r < P; r += kThreads) {
+        int rel = r - pa.root;
+        if (rel < 0) rel += P;
+        const int right_rel = (rel + 1 < P) ? rel + 1 : rel + 1 - P;
+        int step = -1, flag = -1;
+        if (P > 1) {
+            if (right_rel == 0) {
+                step = P;
+                flag = 1;
+            } else if (rel == 0) {
+                step = P;
+                flag = 0;
+            } else if ((right_rel & 1) == 0) {
+                const int span = (int)lowbit((uint32_t)right_rel);
+                step = (right_rel + span > P) ? P - right_rel : span;
+                flag = 1;
+            } else {
+                const int span = (int)lowbit((uint32_t)rel);
+                step = (rel + span > P) ? P - rel : span;
+                flag = 0;
+            }
+        }
+        pa.rel[r] = rel;
+        pa.left[r] = (r + P - 1) % P;
+        pa.right[r] = (r + 1) % P;
+        pa.sw_step[r] = step;
+        pa.sw_flag[r] = flag;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 2: row tables.  One workgroup per step.
+//
+// Scatter level t (distance m = 2^(L-1-t)) [Sec. III-A, Figs. 1-2]: every
+// relative rank rho that is a multiple of 2m and has rho + m < P sends the
+// chunks [rho + m, min(rho + 2m, P)) as one message to rho + m.
+//
+// Ring step i = 1..P-1 [Sec. III-A Fig. 3; Sec. IV listing]: the rank with
+// relative rank rho sends the chunk with relative index (rho - i + 1) mod P to
+// its right neighbour.  NATIVE posts every such send.  TUNED posts it while
+// the sender's step <= P - i and afterwards only if the sender's tail is
+// send-only; the receiver decides symmetrically from its own (step, flag), and
+// the two decisions are compared (they always agree).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
+    __shared__ uint32_t slots32[kWaves];
+    __shared__ uint64_t slots64[kWaves];
+
+    const int P = pa.P;
+    const int s = blockIdx.x;
+    const bool scatter = s < pa.L;
+    const int m = scatter ? (1 << (pa.L - 1 - s)) : 0;
+    const int i = s - pa.L + 1;
+    const int tl = pa.tile_log2;
+
+    Row *rows = pa.rows + (size_t)s * P;
+    uint32_t *tile_ptr = pa.tile_ptr + (size_t)s * (P + 1);
+
+    uint32_t n_rows = 0, n_tiles = 0, n_posted = 0, n_mismatch = 0;
+    uint64_t n_bytes = 0;
+
+    for (int base = 0; base < P; base += kThreads) {
+        const int rho = base + (int)threadIdx.x;
+        bool posted = false, mismatch = false;
+        int dst_rel = 0;
+        uint64_t off = 0, len = 0;
+        if (rho < P) {
+            if (scatter) {
+                if ((rho & (2 * m - 1)) == 0 && rho + m < P) {
+                    dst_rel = rho + m;
+                    const int end = (rho + 2 * m < P) ? rho + 2 * m : P;
+                    off = pa.chunk_off[dst_rel];
+                    len = pa.chunk_off[end] - off;
+                    posted = len > 0;
+                }
+            } else {
+                int c = rho + 1 - i;
+                if (c < 0) c += P;
+                dst_rel = (rho + 1 < P) ? rho + 1 : 0;
+                off = pa.chunk_off[c];
+                len = pa.chunk_len[c];
+                if (pa.algo == 0) {
+                    posted = true;
+                } else {
+                    int snd = rho + pa.root;
+                    if (snd >= P) snd -= P;
+                    int rcv = dst_rel + pa.root;
+                    if (rcv >= P) rcv -= P;
+                    const bool sends = pa.sw_step[snd] <= P - i || pa.sw_flag[snd] == 0;
+                    const bool recvs = pa.sw_step[rcv] <= P - i || pa.sw_flag[rcv] == 1;
+                    posted = sends;
+                    mismatch = sends != recvs;
+                }
+            }
+        }
+        const bool valid = posted && len > 0;
+        uint32_t tiles_here = 0;
+        if (valid) tiles_here = (uint32_t)(((off + len - 1) >> tl) - (off >> tl)) + 1u;
+
+        uint32_t rows_total, tiles_total, posted_total, mismatch_total;
+        uint64_t bytes_total;
+        const uint32_t row_idx = block_exclusive_count(valid, slots32, rows_total);
+        const uint32_t tile_before = block_exclusive_scan<uint32_t>(tiles_here, slots32, tiles_total);
+        (void)block_exclusive_count(posted, slots32, posted_total);
+        (void)block_exclusive_count(mismatch, slots32, mismatch_total);
+        (void)block_exclusive_scan<uint64_t>(valid ? len : 0, slots64, bytes_total);
+
+        if (valid) {
+            int src = rho + pa.root;
+            if (src >= P) src -= P;
+            int dst = dst_rel + pa.root;
+            if (dst >= P) dst -= P;
+            Row r;
+            r.src = (uint32_t)src;
+            r.dst = (uint32_t)dst;
+            r.off = off;
+            r.len = len;
+            rows[n_rows + row_idx] = r;
+            tile_ptr[n_rows + row_idx] = n_tiles + tile_before;
+        }
+        n_rows += rows_total;
+        n_tiles += tiles_total;
+        n_posted += posted_total;
+        n_mismatch += mismatch_total;
+        n_bytes += bytes_total;
+    }
+    if (threadIdx.x == 0) {
+        tile_ptr[n_rows] = n_tiles;
+        pa.step_rows[s] = n_rows;
+        pa.step_tiles[s] = n_tiles;
+        pa.step_posted[s] = n_posted;
+        pa.step_mismatch[s] = n_mismatch;
+        pa.step_bytes[s] = n_bytes;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Kernel 3: tile maps.  grid = (tile slots / 256, steps).  Each lane owns one
+// tile slot of its step and finds, by bisection over the step's exclusive tile
+// scan (staged in LDS when it fits), the row the tile belongs to.
+// ---------------------------------------------------------------------------
+constexpr int kStageMax = 8192;
+
+__global__ __launch_bounds__(kThreads) void plan_tiles(PlanArrays pa) {
+    __shared__ uint32_t stage[kStageMax];
+    const int s = blockIdx.y;
+    const uint32_t n_tiles = pa.step_tiles[s];
+    if (blockIdx.x * (uint32_t)kThreads >= n_tiles) return;  // whole workgroup leaves
+    const uint32_t n_rows = pa.step_rows[s];
+    const uint32_t *ptr = pa.tile_ptr + (size_t)s * (pa.P + 1);
+    if (n_rows + 1 <= (uint32_t)kStageMax) {
+        for (uint32_t k = threadIdx.x; k <= n_rows; k += kThreads) stage[k] = ptr[k];
+        __syncthreads();
+        ptr = stage;
+    }
+    const uint32_t b = blockIdx.x * (uint32_t)kThreads + threadIdx.x;
+    if (b >= n_tiles || b >= pa.tile_cap) return;
+    uint32_t lo = 0, hi = n_rows;  // ptr[lo] <= b < ptr[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (ptr[mid] <= b)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    Tile t;
+    t.row = lo;
+    t.idx = b - ptr[lo];
+    pa.tiles[(size_t)s * pa.tile_cap + b] = t;
+}
+
+}  // namespace
+
+hipError_t launch_plan_kernels(const PlanArrays &pa, hipStream_t stream) {
+    hipLaunchKernelGGL(plan_descriptors, dim3(1), dim3(kThreads), 0, stream, pa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (pa.n_steps == 0) return hipSuccess;
+    hipLaunchKernelGGL(plan_rows, dim3(pa.n_steps), dim3(kThreads), 0, stream, pa);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint32_t gx = (pa.tile_cap + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(plan_tiles, dim3(gx, pa.n_steps), dim3(kThreads), 0, stream, pa);
+    return hipGetLastError();
+}
+
+}  // namespace vbcast

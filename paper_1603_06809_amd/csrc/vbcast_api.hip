@@ -1,0 +1,437 @@
+// Host side of libvbcast: argument checks, device allocations for the plan,
+// the graph that chains table generation and the per-step copy kernels, and
+// the exports.  See include/vbcast.h for the contract of every entry point.
+
+#include "../../include/vbcast.h"
+#include "vbcast_internal.h"
+
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using vbcast::PlanArrays;
+using vbcast::Row;
+using vbcast::Tile;
+
+struct vbcast_comm {
+    int P = 0;
+    size_t buf_bytes = 0;
+    int device = 0;
+    std::vector<void *> host_bases;
+    uint8_t **dev_bases = nullptr;
+};
+
+struct vbcast_plan {
+    const vbcast_comm *comm = nullptr;
+    PlanArrays pa{};
+    void *arena = nullptr;  // one device allocation holding every plan array
+    // per-step counts, read back once at plan time
+    std::vector<uint32_t> step_rows, step_tiles, step_posted, step_mismatch;
+    std::vector<uint64_t> step_bytes;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
+namespace {
+
+thread_local std::string g_hip_msg;
+thread_local std::string g_text;
+std::atomic<int> g_tile_log2{14};
+
+int hip_fail(hipError_t e, const char *what) {
+    g_hip_msg = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();  // clear the sticky slot
+    return VBCAST_ERR_HIP;
+}
+
+#define HIP_TRY(call)                                        \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);    \
+    } while (0)
+
+int ceil_log2_int(int P) {
+    int k = 0;
+    while ((1 << k) < P) ++k;
+    return k;
+}
+
+struct ArenaLayout {
+    size_t total = 0;
+    size_t take(size_t bytes) {
+        const size_t at = total;
+        total += (bytes + 255) & ~size_t(255);
+        return at;
+    }
+};
+
+int launch_steps(const vbcast_plan *plan, int first, int last, hipStream_t stream,
+                 hipEvent_t *marks) {
+    const PlanArrays &pa = plan->pa;
+    for (int s = first; s < last; ++s) {
+        if (marks) HIP_TRY(hipEventRecord(marks[s - first], stream));
+        const uint32_t nt = plan->step_tiles[s];
+        if (nt == 0) continue;
+        HIP_TRY(vbcast::launch_step_copy(pa.rows + (size_t)s * pa.P,
+                                         pa.tiles + (size_t)s * pa.tile_cap,
+                                         plan->comm->dev_bases, nt, pa.tile_log2, stream));
+    }
+    if (marks) HIP_TRY(hipEventRecord(marks[last - first], stream));
+    return VBCAST_SUCCESS;
+}
+
+int build_graph(vbcast_plan *plan) {
+    hipStream_t cap = nullptr;
+    HIP_TRY(hipStreamCreateWithFlags(&cap, hipStreamNonBlocking));
+    int rc = VBCAST_SUCCESS;
+    hipError_t e = hipStreamBeginCapture(cap, hipStreamCaptureModeRelaxed);
+    if (e != hipSuccess) {
+        (void)hipStreamDestroy(cap);
+        return hip_fail(e, "hipStreamBeginCapture");
+    }
+    e = vbcast::launch_plan_kernels(plan->pa, cap);
+    if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
+    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, plan->pa.n_steps, cap, nullptr);
+    hipGraph_t graph = nullptr;
+    e = hipStreamEndCapture(cap, &graph);
+    (void)hipStreamDestroy(cap);
+    if (rc != VBCAST_SUCCESS) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e != hipSuccess) return hip_fail(e, "hipStreamEndCapture");
+    plan->graph = graph;
+    HIP_TRY(hipGraphInstantiate(&plan->exec, graph, nullptr, nullptr, 0));
+    return VBCAST_SUCCESS;
+}
+
+void free_plan(vbcast_plan *plan) {
+    if (!plan) return;
+    if (plan->exec) (void)hipGraphExecDestroy(plan->exec);
+    if (plan->graph) (void)hipGraphDestroy(plan->graph);
+    if (plan->arena) (void)hipFree(plan->arena);
+    delete plan;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vbcast_set_tile_bytes(size_t tile_bytes) {
+    for (int k = 12; k <= 16; ++k)
+        if (tile_bytes == (size_t(1) << k)) {
+            g_tile_log2.store(k);
+            return VBCAST_SUCCESS;
+        }
+    return VBCAST_ERR_ARG;
+}
+
+int vbcast_comm_create(int P, void *const *rank_bufs, size_t buf_bytes, vbcast_comm **out) {
+    if (!out) return VBCAST_ERR_ARG;
+    *out = nullptr;
+    if (!rank_bufs || P < 1 || P > VBCAST_MAX_RANKS) return VBCAST_ERR_ARG;
+    for (int r = 0; r < P; ++r) {
+        if (!rank_bufs[r]) return VBCAST_ERR_ARG;
+        if (reinterpret_cast<uintptr_t>(rank_bufs[r]) & 15u) return VBCAST_ERR_ALIGN;
+    }
+    vbcast_comm *c = new (std::nothrow) vbcast_comm;
+    if (!c) return VBCAST_ERR_NOMEM;
+    c->P = P;
+    c->buf_bytes = buf_bytes;
+    c->host_bases.assign(rank_bufs, rank_bufs + P);
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&c->dev_bases), sizeof(void *) * P);
+    if (e == hipSuccess)
+        e = hipMemcpy(c->dev_bases, c->host_bases.data(), sizeof(void *) * P, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (c->dev_bases) (void)hipFree(c->dev_bases);
+        delete c;
+        return e == hipErrorOutOfMemory ? VBCAST_ERR_NOMEM : hip_fail(e, "vbcast_comm_create");
+    }
+    *out = c;
+    return VBCAST_SUCCESS;
+}
+
+int vbcast_comm_destroy(vbcast_comm *comm) {
+    if (!comm) return VBCAST_ERR_ARG;
+    hipError_t e = comm->dev_bases ? hipFree(comm->dev_bases) : hipSuccess;
+    delete comm;
+    if (e != hipSuccess) return hip_fail(e, "hipFree");
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int root, int algo,
+               void *hip_stream, vbcast_plan **out) {
+    if (!out) return VBCAST_ERR_ARG;
+    *out = nullptr;
+    if (!comm) return VBCAST_ERR_ARG;
+    if (algo != VBCAST_NATIVE && algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
+    const int P = comm->P;
+    if (root < 0 || root >= P) return VBCAST_ERR_ROOT;
+    if (dtype_size != 0 && count > SIZE_MAX / dtype_size) return VBCAST_ERR_COUNT;
+    const uint64_t n = (uint64_t)count * (uint64_t)dtype_size;
+    if (n > comm->buf_bytes) return VBCAST_ERR_COUNT;
+    const int tile_log2 = g_tile_log2.load();
+    const uint64_t tile_cap64 = (n >> tile_log2) + 2ull * (uint64_t)P + 1ull;
+    if (tile_cap64 >= (1ull << 31)) return VBCAST_ERR_COUNT;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    vbcast_plan *plan = new (std::nothrow) vbcast_plan;
+    if (!plan) return VBCAST_ERR_NOMEM;
+    plan->comm = comm;
+    PlanArrays &pa = plan->pa;
+    pa.P = P;
+    pa.root = root;
+    pa.algo = algo;
+    pa.L = ceil_log2_int(P);
+    pa.n_steps = P > 1 ? pa.L + P - 1 : 0;
+    pa.tile_log2 = tile_log2;
+    pa.tile_cap = (uint32_t)tile_cap64;
+    pa.n = n;
+    pa.ss = (n + (uint64_t)P - 1) / (uint64_t)P;
+
+    const size_t S = (size_t)pa.n_steps, Pz = (size_t)P;
+    ArenaLayout lay;
+    const size_t o_chunk_off = lay.take(sizeof(uint64_t) * (Pz + 1));
+    const size_t o_chunk_len = lay.take(sizeof(uint64_t) * Pz);
+    const size_t o_rel = lay.take(sizeof(int32_t) * Pz);
+    const size_t o_left = lay.take(sizeof(int32_t) * Pz);
+    const size_t o_right = lay.take(sizeof(int32_t) * Pz);
+    const size_t o_sw_step = lay.take(sizeof(int32_t) * Pz);
+    const size_t o_sw_flag = lay.take(sizeof(int32_t) * Pz);
+    const size_t o_rows = lay.take(sizeof(Row) * S * Pz);
+    const size_t o_tile_ptr = lay.take(sizeof(uint32_t) * S * (Pz + 1));
+    const size_t o_tiles = lay.take(sizeof(Tile) * S * (size_t)pa.tile_cap);
+    const size_t o_step_rows = lay.take(sizeof(uint32_t) * S);
+    const size_t o_step_tiles = lay.take(sizeof(uint32_t) * S);
+    const size_t o_step_posted = lay.take(sizeof(uint32_t) * S);
+    const size_t o_step_mismatch = lay.take(sizeof(uint32_t) * S);
+    const size_t o_step_bytes = lay.take(sizeof(uint64_t) * S);
+
+    hipError_t e = hipMalloc(&plan->arena, lay.total);
+    if (e != hipSuccess) {
+        delete plan;
+        if (e == hipErrorOutOfMemory) {
+            (void)hipGetLastError();
+            return VBCAST_ERR_NOMEM;
+        }
+        return hip_fail(e, "hipMalloc(plan)");
+    }
+    char *base = static_cast<char *>(plan->arena);
+    pa.chunk_off = reinterpret_cast<uint64_t *>(base + o_chunk_off);
+    pa.chunk_len = reinterpret_cast<uint64_t *>(base + o_chunk_len);
+    pa.rel = reinterpret_cast<int32_t *>(base + o_rel);
+    pa.left = reinterpret_cast<int32_t *>(base + o_left);
+    pa.right = reinterpret_cast<int32_t *>(base + o_right);
+    pa.sw_step = reinterpret_cast<int32_t *>(base + o_sw_step);
+    pa.sw_flag = reinterpret_cast<int32_t *>(base + o_sw_flag);
+    pa.rows = reinterpret_cast<Row *>(base + o_rows);
+    pa.tile_ptr = reinterpret_cast<uint32_t *>(base + o_tile_ptr);
+    pa.tiles = reinterpret_cast<Tile *>(base + o_tiles);
+    pa.step_rows = reinterpret_cast<uint32_t *>(base + o_step_rows);
+    pa.step_tiles = reinterpret_cast<uint32_t *>(base + o_step_tiles);
+    pa.step_posted = reinterpret_cast<uint32_t *>(base + o_step_posted);
+    pa.step_mismatch = reinterpret_cast<uint32_t *>(base + o_step_mismatch);
+    pa.step_bytes = reinterpret_cast<uint64_t *>(base + o_step_bytes);
+
+    int rc = VBCAST_SUCCESS;
+    e = vbcast::launch_plan_kernels(pa, stream);
+    if (e != hipSuccess) rc = hip_fail(e, "plan kernels");
+
+    plan->step_rows.resize(S);
+    plan->step_tiles.resize(S);
+    plan->step_posted.resize(S);
+    plan->step_mismatch.resize(S);
+    plan->step_bytes.resize(S);
+    auto pull = [&](void *dst, const void *src, size_t bytes) {
+        if (rc != VBCAST_SUCCESS || bytes == 0) return;
+        hipError_t ee = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, stream);
+        if (ee != hipSuccess) rc = hip_fail(ee, "hipMemcpyAsync(step counts)");
+    };
+    pull(plan->step_rows.data(), pa.step_rows, sizeof(uint32_t) * S);
+    pull(plan->step_tiles.data(), pa.step_tiles, sizeof(uint32_t) * S);
+    pull(plan->step_posted.data(), pa.step_posted, sizeof(uint32_t) * S);
+    pull(plan->step_mismatch.data(), pa.step_mismatch, sizeof(uint32_t) * S);
+    pull(plan->step_bytes.data(), pa.step_bytes, sizeof(uint64_t) * S);
+    if (rc == VBCAST_SUCCESS) {
+        e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) rc = hip_fail(e, "hipStreamSynchronize(plan)");
+    }
+    if (rc == VBCAST_SUCCESS) {
+        for (size_t s = 0; s < S; ++s)
+            if (plan->step_tiles[s] > pa.tile_cap || plan->step_rows[s] > (uint32_t)P) {
+                g_hip_msg = "internal: per-step counts exceed table capacity";
+                rc = VBCAST_ERR_HIP;
+            }
+    }
+    if (rc == VBCAST_SUCCESS) rc = build_graph(plan);
+    if (rc != VBCAST_SUCCESS) {
+        free_plan(plan);
+        return rc;
+    }
+    *out = plan;
+    return VBCAST_SUCCESS;
+}
+
+int bcast_run(const vbcast_plan *plan, void *hip_stream) {
+    if (!plan || !plan->exec) return VBCAST_ERR_ARG;
+    HIP_TRY(hipGraphLaunch(plan->exec, static_cast<hipStream_t>(hip_stream)));
+    return VBCAST_SUCCESS;
+}
+
+int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stream) {
+    if (!plan) return VBCAST_ERR_ARG;
+    if (first < 0 || first > last || last > plan->pa.n_steps) return VBCAST_ERR_ARG;
+    return launch_steps(plan, first, last, static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hip_stream,
+                          float *step_ms) {
+    if (!plan || !step_ms) return VBCAST_ERR_ARG;
+    if (first < 0 || first > last || last > plan->pa.n_steps) return VBCAST_ERR_ARG;
+    const int k = last - first;
+    if (k == 0) return VBCAST_SUCCESS;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    std::vector<hipEvent_t> marks((size_t)k + 1, nullptr);
+    int rc = VBCAST_SUCCESS;
+    for (auto &m : marks) {
+        hipError_t e = hipEventCreate(&m);
+        if (e != hipSuccess) {
+            rc = hip_fail(e, "hipEventCreate");
+            break;
+        }
+    }
+    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, first, last, stream, marks.data());
+    if (rc == VBCAST_SUCCESS) {
+        hipError_t e = hipEventSynchronize(marks[k]);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventSynchronize");
+    }
+    if (rc == VBCAST_SUCCESS) {
+        for (int i = 0; i < k; ++i) {
+            step_ms[i] = 0.f;
+            if (plan->step_tiles[first + i] == 0) continue;
+            hipError_t e = hipEventElapsedTime(&step_ms[i], marks[i], marks[i + 1]);
+            if (e != hipSuccess) {
+                rc = hip_fail(e, "hipEventElapsedTime");
+                break;
+            }
+        }
+    }
+    for (auto &m : marks)
+        if (m) (void)hipEventDestroy(m);
+    return rc;
+}
+
+int bcast_plan_info(const vbcast_plan *plan, vbcast_plan_info *info) {
+    if (!plan || !info) return VBCAST_ERR_ARG;
+    const PlanArrays &pa = plan->pa;
+    std::memset(info, 0, sizeof(*info));
+    info->P = pa.P;
+    info->root = pa.root;
+    info->algo = pa.algo;
+    info->n_scatter_steps = pa.n_steps ? pa.L : 0;
+    info->n_steps = pa.n_steps;
+    info->tile_bytes = 1 << pa.tile_log2;
+    info->n = pa.n;
+    info->ss = pa.ss;
+    for (int s = 0; s < pa.n_steps; ++s) {
+        const bool scatter = s < pa.L;
+        (scatter ? info->scatter_rows : info->ring_rows) += plan->step_rows[s];
+        (scatter ? info->scatter_bytes : info->ring_bytes) += plan->step_bytes[s];
+        if (!scatter) info->ring_msgs_issued += plan->step_posted[s];
+        info->pairing_mismatches += plan->step_mismatch[s];
+        info->n_tiles += plan->step_tiles[s];
+    }
+    info->bytes_moved = info->scatter_bytes + info->ring_bytes;
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_export(const vbcast_plan *plan, uint64_t *step_ptr, uint32_t *src, uint32_t *dst,
+                      uint64_t *off, uint64_t *len, uint64_t *step_bytes) {
+    if (!plan) return VBCAST_ERR_ARG;
+    const PlanArrays &pa = plan->pa;
+    uint64_t at = 0;
+    std::vector<Row> tmp;
+    for (int s = 0; s < pa.n_steps; ++s) {
+        const uint32_t nr = plan->step_rows[s];
+        if (step_ptr) step_ptr[s] = at;
+        if (step_bytes) step_bytes[s] = plan->step_bytes[s];
+        if (nr && (src || dst || off || len)) {
+            tmp.resize(nr);
+            HIP_TRY(hipMemcpy(tmp.data(), pa.rows + (size_t)s * pa.P, sizeof(Row) * nr,
+                              hipMemcpyDeviceToHost));
+            for (uint32_t k = 0; k < nr; ++k) {
+                if (src) src[at + k] = tmp[k].src;
+                if (dst) dst[at + k] = tmp[k].dst;
+                if (off) off[at + k] = tmp[k].off;
+                if (len) len[at + k] = tmp[k].len;
+            }
+        }
+        at += nr;
+    }
+    if (step_ptr) step_ptr[pa.n_steps] = at;
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_export_desc(const vbcast_plan *plan, uint64_t *chunk_off, uint64_t *chunk_len,
+                           int32_t *rel, int32_t *left, int32_t *right, int32_t *sw_step,
+                           int32_t *sw_flag) {
+    if (!plan) return VBCAST_ERR_ARG;
+    const PlanArrays &pa = plan->pa;
+    const size_t P = (size_t)pa.P;
+    if (chunk_off)
+        HIP_TRY(hipMemcpy(chunk_off, pa.chunk_off, sizeof(uint64_t) * (P + 1), hipMemcpyDeviceToHost));
+    if (chunk_len)
+        HIP_TRY(hipMemcpy(chunk_len, pa.chunk_len, sizeof(uint64_t) * P, hipMemcpyDeviceToHost));
+    if (rel) HIP_TRY(hipMemcpy(rel, pa.rel, sizeof(int32_t) * P, hipMemcpyDeviceToHost));
+    if (left) HIP_TRY(hipMemcpy(left, pa.left, sizeof(int32_t) * P, hipMemcpyDeviceToHost));
+    if (right) HIP_TRY(hipMemcpy(right, pa.right, sizeof(int32_t) * P, hipMemcpyDeviceToHost));
+    if (sw_step) HIP_TRY(hipMemcpy(sw_step, pa.sw_step, sizeof(int32_t) * P, hipMemcpyDeviceToHost));
+    if (sw_flag) HIP_TRY(hipMemcpy(sw_flag, pa.sw_flag, sizeof(int32_t) * P, hipMemcpyDeviceToHost));
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles,
+                            uint32_t *tile_row, uint32_t *tile_idx) {
+    if (!plan || !n_tiles) return VBCAST_ERR_ARG;
+    const PlanArrays &pa = plan->pa;
+    if (step < 0 || step >= pa.n_steps) return VBCAST_ERR_ARG;
+    const uint32_t nt = plan->step_tiles[step];
+    *n_tiles = nt;
+    if (nt && (tile_row || tile_idx)) {
+        std::vector<Tile> tmp(nt);
+        HIP_TRY(hipMemcpy(tmp.data(), pa.tiles + (size_t)step * pa.tile_cap, sizeof(Tile) * nt,
+                          hipMemcpyDeviceToHost));
+        for (uint32_t k = 0; k < nt; ++k) {
+            if (tile_row) tile_row[k] = tmp[k].row;
+            if (tile_idx) tile_idx[k] = tmp[k].idx;
+        }
+    }
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_destroy(vbcast_plan *plan) {
+    if (!plan) return VBCAST_ERR_ARG;
+    free_plan(plan);
+    return VBCAST_SUCCESS;
+}
+
+const char *bcast_strerror(int code) {
+    switch (code) {
+        case VBCAST_SUCCESS: return "success";
+        case VBCAST_ERR_ARG: return "invalid argument";
+        case VBCAST_ERR_ROOT: return "root is not a rank of the communicator";
+        case VBCAST_ERR_COUNT: return "message size overflows or exceeds the rank buffers";
+        case VBCAST_ERR_ALIGN: return "rank buffer is not 16-byte aligned";
+        case VBCAST_ERR_NOMEM: return "out of memory";
+        case VBCAST_ERR_HIP:
+            g_text = "HIP runtime failure: " + g_hip_msg;
+            return g_text.c_str();
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the HIP sources of libvbcast (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vbcast {
+
+// One transfer of a step: copy `len` bytes at byte offset `off` from rank
+// `src`'s buffer to the same offset in rank `dst`'s buffer.
+struct Row {
+    uint32_t src;
+    uint32_t dst;
+    uint64_t off;
+    uint64_t len;
+};
+static_assert(sizeof(Row) == 24, "Row layout");
+
+// One copy tile: the part of row `row` inside the `idx`-th tile-aligned window
+// the row touches.
+struct Tile {
+    uint32_t row;
+    uint32_t idx;
+};
+
+// Everything the generation kernels read and write, all device pointers.
+// Per-step arrays are indexed by step; row and tile arrays have a fixed stride
+// per step (`P` rows, `P + 1` tile-scan entries, `tile_cap` tiles).
+struct PlanArrays {
+    int32_t P, root, algo;
+    int32_t L;          // scatter levels = ceil(log2 P)
+    int32_t n_steps;    // L + P - 1 (0 when P == 1)
+    int32_t tile_log2;
+    uint32_t tile_cap;  // tile slots per step
+    uint64_t n, ss;
+
+    uint64_t *chunk_off;  // [P + 1]
+    uint64_t *chunk_len;  // [P]
+    int32_t *rel, *left, *right, *sw_step, *sw_flag;  // [P], by absolute rank
+
+    Row *rows;            // [n_steps][P]
+    uint32_t *tile_ptr;   // [n_steps][P + 1] exclusive scan of tiles per row
+    Tile *tiles;          // [n_steps][tile_cap]
+
+    uint32_t *step_rows;    // [n_steps]
+    uint32_t *step_tiles;   // [n_steps]
+    uint32_t *step_posted;  // [n_steps] sends posted, zero-length included
+    uint32_t *step_mismatch;  // [n_steps] sender/receiver decisions that disagree
+    uint64_t *step_bytes;   // [n_steps]
+};
+
+// Enqueue the three generation kernels (descriptors, rows, tile maps).
+hipError_t launch_plan_kernels(const PlanArrays &pa, hipStream_t stream);
+
+// Enqueue the copy kernel of one step; `n_tiles` > 0 workgroups.
+hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
+                            uint32_t n_tiles, int tile_log2, hipStream_t stream);
+
+}  // namespace vbcast

@@ -74,17 +74,26 @@ def splitmix64_word(key: int, k: int) -> int:
     return z ^ (z >> 31)
 
 
-def bytes_numpy(seed: int, stream: int, nbytes: int) -> np.ndarray:
-    """First ``nbytes`` bytes of a stream as a numpy uint8 array."""
-    nwords = (nbytes + 7) // 8
+def bytes_numpy(seed: int, stream: int, nbytes: int, start: int = 0) -> np.ndarray:
+    """Bytes ``[start, start + nbytes)`` of a stream as a numpy uint8 array."""
+    if start:
+        first = start // 8
+        head = start - first * 8
+        words = bytes_numpy_words(seed, stream, first, (head + nbytes + 7) // 8)
+        return words.view(np.uint8)[head:head + nbytes].copy()
+    return bytes_numpy_words(seed, stream, 0, (nbytes + 7) // 8).view(np.uint8)[:nbytes].copy()
+
+
+def bytes_numpy_words(seed: int, stream: int, first_word: int, nwords: int) -> np.ndarray:
+    """Words ``[first_word, first_word + nwords)`` of a stream, little-endian."""
     key = np.uint64(stream_key(seed, stream))
     with np.errstate(over="ignore"):
-        k = np.arange(1, nwords + 1, dtype=np.uint64)
+        k = np.arange(first_word + 1, first_word + nwords + 1, dtype=np.uint64)
         z = key + k * np.uint64(_GOLDEN)
         z = (z ^ (z >> np.uint64(30))) * np.uint64(_MIX1)
         z = (z ^ (z >> np.uint64(27))) * np.uint64(_MIX2)
         z = z ^ (z >> np.uint64(31))
-    return z.astype("<u8").view(np.uint8)[:nbytes].copy()
+    return z.astype("<u8")
 
 
 def _s64(x: int) -> int:

@@ -1,0 +1,83 @@
+"""The C-ABI library loads, exports every function the header declares, and
+rejects invalid arguments before touching a device.  CPU only: no call here
+reaches a GPU."""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1603_06809_amd import vbcast as V
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vbcast.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:vbcast|bcast)_\w+)\s*\(", text)))
+
+
+def test_library_is_built():
+    assert os.path.exists(V.LIB_PATH), "build the library first (see __graft_entry__.build)"
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert "bcast_plan" in names and "bcast_run" in names and "vbcast_comm_create" in names
+    lib = V.lib()
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(V.EXPORTS) == names
+
+
+def test_plan_info_struct_matches_header():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct vbcast_plan_info \{(.*?)\} vbcast_plan_info;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        ctype, names = decl.split(None, 1)
+        fields += [(n.strip(), ctype) for n in names.split(",")]
+    want = {"int32_t": C.c_int32, "uint64_t": C.c_uint64}
+    assert [(n, want[t]) for n, t in fields] == [(n, t) for n, t in V.PlanInfo._fields_]
+
+
+def test_invalid_arguments_are_rejected_without_a_device():
+    lib = V.lib()
+    h = C.c_void_p()
+    one = (C.c_void_p * 1)(0x1000)
+    assert lib.vbcast_comm_create(0, one, 16, C.byref(h)) == V.ERR_ARG
+    assert lib.vbcast_comm_create(-3, one, 16, C.byref(h)) == V.ERR_ARG
+    assert lib.vbcast_comm_create(8193, one, 16, C.byref(h)) == V.ERR_ARG
+    assert lib.vbcast_comm_create(1, None, 16, C.byref(h)) == V.ERR_ARG
+    assert lib.vbcast_comm_create(1, one, 16, None) == V.ERR_ARG
+    null = (C.c_void_p * 1)(None)
+    assert lib.vbcast_comm_create(1, null, 16, C.byref(h)) == V.ERR_ARG
+    odd = (C.c_void_p * 2)(0x1000, 0x2008)
+    assert lib.vbcast_comm_create(2, odd, 16, C.byref(h)) == V.ERR_ALIGN
+    assert not h.value
+    assert lib.vbcast_comm_destroy(None) == V.ERR_ARG
+    assert lib.bcast_plan(None, 1, 1, 0, 0, None, C.byref(h)) == V.ERR_ARG
+    assert lib.bcast_plan(None, 1, 1, 0, 0, None, None) == V.ERR_ARG
+    assert lib.bcast_run(None, None) == V.ERR_ARG
+    assert lib.bcast_run_steps(None, 0, 0, None) == V.ERR_ARG
+    assert lib.bcast_plan_info(None, None) == V.ERR_ARG
+    assert lib.bcast_plan_destroy(None) == V.ERR_ARG
+    assert lib.vbcast_set_tile_bytes(1000) == V.ERR_ARG
+    assert lib.vbcast_set_tile_bytes(1 << 20) == V.ERR_ARG
+    assert lib.vbcast_set_tile_bytes(1 << 14) == V.SUCCESS
+
+
+def test_error_texts():
+    for code in range(7):
+        assert V.bcast_strerror(code)
+    assert "unknown" in V.bcast_strerror(99)
+    with pytest.raises(V.VbcastError) as e:
+        V.Comm([0x1008], 16)
+    assert e.value.code == V.ERR_ALIGN

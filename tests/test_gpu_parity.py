@@ -1,0 +1,322 @@
+"""GPU path vs CPU oracle, bit for bit: tables, descriptors, byte counts, the
+state after every step and the final state.  Everything goes through the C-ABI
+library (via the ctypes binding)."""
+
+import numpy as np
+import pytest
+
+from oracle import bcast_oracle as O
+from paper_1603_06809_amd import inputs as I
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = [O.NATIVE, O.TUNED]
+
+
+@pytest.fixture(scope="module")
+def V():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_1603_06809_amd import vbcast
+    vbcast.lib()
+    vbcast.vbcast_set_tile_bytes(1 << 14)
+    return vbcast
+
+
+def sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def make(V, w, algo, pad=64):
+    state = H.device_buffers(w, pad)
+    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
+    plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+    return state, comm, plan
+
+
+def check_tables(plan, sched):
+    info = plan.info()
+    assert (info.P, info.root, info.n) == (sched.P, sched.root, sched.n)
+    assert info.ss == sched.ss
+    assert info.n_steps == sched.n_steps
+    assert info.n_scatter_steps == (sched.n_scatter_steps if sched.P > 1 else 0)
+    rows = sched.step_rows()
+    nsc = sched.n_scatter_steps
+    assert info.scatter_rows == sum(rows[:nsc]) and info.ring_rows == sum(rows[nsc:])
+    assert info.scatter_bytes == sched.scatter_bytes
+    assert info.ring_bytes == sched.ring_bytes
+    assert info.bytes_moved == sched.bytes_moved
+    assert info.ring_msgs_issued == sched.ring_msgs_issued
+    assert info.pairing_mismatches == 0
+    t = plan.export()
+    want_ptr = np.concatenate([[0], np.cumsum(rows)]).astype(np.uint64)
+    assert np.array_equal(t.step_ptr, want_ptr)
+    assert np.array_equal(t.step_bytes, np.array(sched.step_bytes(), dtype=np.uint64))
+    flat = [r for step in sched.steps for r in step]
+    want = np.array(flat, dtype=np.uint64).reshape(-1, 4)
+    assert np.array_equal(t.src.astype(np.uint64), want[:, 0])
+    assert np.array_equal(t.dst.astype(np.uint64), want[:, 1])
+    assert np.array_equal(t.off, want[:, 2])
+    assert np.array_equal(t.len, want[:, 3])
+    return t
+
+
+def check_desc(plan, w):
+    d = plan.export_desc()
+    P, root, n = w.P, w.root, w.n
+    ext = [O.chunk_extent(c, n, P) for c in range(P)]
+    assert [int(x) for x in d["chunk_len"]] == [e[1] for e in ext]
+    run = 0
+    for c in range(P):
+        assert int(d["chunk_off"][c]) == run
+        if ext[c][1] > 0:
+            assert run == ext[c][0]
+        run += ext[c][1]
+    assert int(d["chunk_off"][P]) == n
+    for r in range(P):
+        rel = O.relative_rank(r, root, P)
+        assert d["rel"][r] == rel
+        assert d["left"][r] == (P + r - 1) % P and d["right"][r] == (r + 1) % P
+        sw = O.tuned_switch(rel, P)
+        assert (d["sw_step"][r], d["sw_flag"][r]) == (sw if sw else (-1, -1))
+
+
+def check_tiles(plan, t, steps):
+    tb = plan.info().tile_bytes
+    for s in steps:
+        row, idx = plan.export_tiles(s)
+        rows = t.rows_of(s)
+        want = []
+        for k, (_s, _d, off, ln) in enumerate(rows):
+            nt = (off + ln - 1) // tb - off // tb + 1
+            want += [(k, j) for j in range(nt)]
+        assert list(zip(row.tolist(), idx.tolist())) == want
+
+
+# ------------------------------------------------------------------ small and edge cases
+
+EDGE = [(P, root, n)
+        for P in (1, 2, 3, 5, 7, 8, 13, 16, 33)
+        for root in sorted({0, P - 1})
+        for n in sorted({0, 1, 15, 16, 17, P - 1, P + 1, 1000, 4097, 70_001})]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_edge_cases_every_step(V, algo):
+    """Tiny and degenerate shapes: one rank, empty message, fewer bytes than
+    ranks (empty chunks), lengths around the 16-byte word."""
+    for (P, root, n) in EDGE:
+        w = I.Workload(f"edge_{P}_{root}_{n}", P, root, n, seed=1000 + P * 131 + n)
+        state, comm, plan = make(V, w, algo, pad=40)
+        sched = O.build_schedule(P, root, n, algo)
+        check_tables(plan, sched)
+        check_desc(plan, w)
+        ref = H.host_buffers(w, pad=40)
+        for s in range(sched.n_steps):
+            plan.run_steps(s, s + 1)
+            O.apply_step(ref, sched.steps[s])
+            got = state.cpu().numpy()
+            assert np.array_equal(got, np.stack(ref)), (P, root, n, algo, s)
+        # and the graph from a fresh state
+        H.refill(state, w)
+        plan.run()
+        sync()
+        want = O.broadcast_definition(H.host_buffers(w, pad=40), root, n)
+        assert np.array_equal(state.cpu().numpy(), np.stack(want)), (P, root, n, algo)
+        plan.destroy()
+        comm.destroy()
+
+
+# ------------------------------------------------------------------ the workloads
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("name", ["P10_n512K", "P24_n4M"])
+def test_state_after_every_step(V, name, algo):
+    w = I.workload(name)
+    state, comm, plan = make(V, w, algo)
+    sched = O.build_schedule(w.P, w.root, w.n, algo)
+    t = check_tables(plan, sched)
+    check_desc(plan, w)
+    check_tiles(plan, t, range(sched.n_steps))
+    ref = H.host_buffers(w)
+    for s in range(sched.n_steps):
+        plan.run_steps(s, s + 1)
+        O.apply_step(ref, sched.steps[s])
+        assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (name, algo, s)
+    want = O.broadcast_definition(H.host_buffers(w), w.root, w.n)
+    assert np.array_equal(np.stack(ref), np.stack(want))
+    plan.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("name", ["P64_n16M", "P96_n12M_ragged"])
+def test_state_at_sampled_steps(V, name, algo):
+    w = I.workload(name)
+    state, comm, plan = make(V, w, algo)
+    sched = O.build_schedule(w.P, w.root, w.n, algo)
+    t = check_tables(plan, sched)
+    check_desc(plan, w)
+    nsc, S = sched.n_scatter_steps, sched.n_steps
+    check_tiles(plan, t, [0, nsc - 1, nsc, S - 1])
+    ref = H.host_buffers(w)
+    stops = sorted({1, nsc, nsc + 1, nsc + 2, nsc + (w.P - 1) // 2, S - 1, S})
+    done = 0
+    for stop in stops:
+        plan.run_steps(done, stop)
+        O.run_steps(ref, sched, done, stop)
+        done = stop
+        got = state.cpu().numpy()
+        for r in range(w.P):
+            assert np.array_equal(got[r], ref[r]), (name, algo, stop, r)
+    plan.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("name", ["P10_n512K", "P24_n4M", "P64_n16M", "P96_n12M_ragged"])
+def test_graph_run_final_state(V, name, algo):
+    """bcast_run (the graph) from a fresh state, twice; the second launch
+    regenerates the tables and must give the same result."""
+    w = I.workload(name)
+    state, comm, plan = make(V, w, algo)
+    want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+    for _ in range(2):
+        H.refill(state, w)
+        V.bcast_run(plan)
+        sync()
+        assert np.array_equal(state.cpu().numpy(), want)
+    sched = O.build_schedule(w.P, w.root, w.n, algo)
+    check_tables(plan, sched)   # tables after regeneration inside the graph
+    plan.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("tile", [4096, 8192, 32768, 65536])
+def test_other_tile_sizes(V, tile):
+    w = I.workload("P24_n4M")
+    V.vbcast_set_tile_bytes(tile)
+    try:
+        for algo in ALGOS:
+            state, comm, plan = make(V, w, algo)
+            assert plan.info().tile_bytes == tile
+            sched = O.build_schedule(w.P, w.root, w.n, algo)
+            t = check_tables(plan, sched)
+            check_tiles(plan, t, [0, sched.n_scatter_steps, sched.n_steps - 1])
+            ref = H.host_buffers(w)
+            nsc = sched.n_scatter_steps
+            for (a, b) in [(0, nsc), (nsc, nsc + 3), (nsc + 3, sched.n_steps)]:
+                plan.run_steps(a, b)
+                O.run_steps(ref, sched, a, b)
+                assert np.array_equal(state.cpu().numpy(), np.stack(ref))
+            plan.destroy()
+            comm.destroy()
+    finally:
+        V.vbcast_set_tile_bytes(1 << 14)
+
+
+def test_timed_steps_report_a_time_per_step(V):
+    w = I.workload("P24_n4M")
+    state, comm, plan = make(V, w, O.TUNED)
+    ms = plan.run_steps_timed(0, plan.info().n_steps)
+    assert ms.shape == (plan.info().n_steps,) and (ms > 0).all()
+    want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+    assert np.array_equal(state.cpu().numpy(), want)
+    plan.destroy()
+    comm.destroy()
+
+
+def test_errors_on_device(V):
+    import torch
+    bufs = [torch.zeros(256, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    comm = V.Comm.from_tensors(bufs)
+    for args, code in [((16, 1, 4, V.NATIVE), V.ERR_ROOT), ((16, 1, -1, V.NATIVE), V.ERR_ROOT),
+                       ((257, 1, 0, V.NATIVE), V.ERR_COUNT), ((1 << 62, 8, 0, V.TUNED), V.ERR_COUNT),
+                       ((16, 1, 0, 2), V.ERR_ARG)]:
+        with pytest.raises(V.VbcastError) as e:
+            V.bcast_plan(comm, *args)
+        assert e.value.code == code
+    plan = V.bcast_plan(comm, 256, 1, 0, V.TUNED)
+    for (a, b) in [(-1, 2), (3, 2), (0, plan.info().n_steps + 1)]:
+        with pytest.raises(V.VbcastError) as e:
+            plan.run_steps(a, b)
+        assert e.value.code == V.ERR_ARG
+    plan.destroy()
+    comm.destroy()
+
+
+# ------------------------------------------------------------------ the large workload
+
+@pytest.fixture(scope="module")
+def big(V):
+    """P = 513 ranks x 128 MiB: ~64 GiB of rank buffers, allocated once."""
+    w = I.workload("P513_n128M")
+    state = H.device_buffers(w, pad=64)
+    yield w, state
+    del state
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_large_workload_tables(V, big, algo):
+    w, state = big
+    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
+    plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+    sched = O.build_schedule(w.P, w.root, w.n, algo)
+    t = check_tables(plan, sched)
+    check_desc(plan, w)
+    check_tiles(plan, t, [0, 9, 10, sched.n_steps - 1])
+    plan.destroy()
+    comm.destroy()
+
+
+def expected_rows(w, sched, k, ranks, stride):
+    """State of the given ranks after k steps, from the oracle's ownership form."""
+    has = O.ownership_after(sched, k)
+    msg = I.message_numpy(w)
+    out = {}
+    for r in ranks:
+        row = H.host_row(w, r, stride)
+        for c in range(w.P):
+            if has[r, c]:
+                d, cnt = O.chunk_extent(c, w.n, w.P)
+                row[d:d + cnt] = msg[d:d + cnt]
+        out[r] = row
+    return out
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_large_workload_state(V, big, algo):
+    """Sampled ranks compared whole at sampled steps (state from the oracle's
+    chunk-ownership form), then every rank compared whole against the message
+    after the graph run."""
+    w, state = big
+    H.refill(state, w)
+    stride = state.shape[1]
+    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], stride)
+    plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+    sched = O.build_schedule(w.P, w.root, w.n, algo)
+    nsc, S = sched.n_scatter_steps, sched.n_steps
+    ranks = [w.root, (w.root + 1) % w.P, (w.root + 256) % w.P, (w.root + 384) % w.P,
+             (w.root - 1) % w.P, 0, 300]
+    done = 0
+    for stop in [nsc, nsc + 1, nsc + 200, S - 1]:
+        plan.run_steps(done, stop)
+        done = stop
+        sync()
+        want = expected_rows(w, sched, stop, ranks, stride)
+        for r in ranks:
+            assert np.array_equal(state[r].cpu().numpy(), want[r]), (algo, stop, r)
+    # the whole broadcast through the graph, from a fresh state
+    H.refill(state, w)
+    V.bcast_run(plan)
+    sync()
+    msg = I.message_numpy(w)
+    for r in range(w.P):
+        got = state[r].cpu().numpy()
+        assert np.array_equal(got[: w.n], msg), (algo, r)
+        tail = H.host_tail(w, r, stride)
+        assert np.array_equal(got[w.n:], tail), (algo, r)
+    plan.destroy()
+    comm.destroy()

@@ -25,6 +25,9 @@ def test_numpy_torch_python_agree():
         key = I.stream_key(seed, stream)
         ref = b"".join(I.splitmix64_word(key, k).to_bytes(8, "little") for k in range((nbytes + 7) // 8))
         assert a.tobytes() == ref[:nbytes]
+        for start in (0, 1, 8, 13, nbytes // 2):
+            if start <= nbytes:
+                assert np.array_equal(I.bytes_numpy(seed, stream, nbytes - start, start), a[start:])
 
 
 def test_streams_differ_and_are_uniform():
