@@ -57,6 +57,9 @@ typedef struct vbcast_plan vbcast_plan; /* tables, tile maps, instantiated graph
 
 enum { VBCAST_NATIVE = 0, VBCAST_TUNED = 1 };
 
+/* How bcast_run executes the ring phase (see vbcast_set_ring_executor). */
+enum { VBCAST_RING_STEPS = 0, VBCAST_RING_CHAINS = 1 };
+
 enum {
     VBCAST_SUCCESS = 0,
     VBCAST_ERR_ARG = 1,   /* null pointer, P < 1, bad algo, bad step range, bad option */
@@ -93,7 +96,7 @@ int vbcast_comm_destroy(vbcast_comm *comm);
  * scatter-level tables [Sec. III-A, Figs. 1-2], the ring-step tables
  * [Sec. III-A Fig. 3 for NATIVE; Sec. IV Figs. 4-5 for TUNED], and for every
  * step the map from copy tiles to rows.  Then record one graph that holds the
- * table-generation kernels followed by one copy kernel per step.
+ * table-generation kernels followed by the copy kernels.
  *   comm        communicator; must outlive the plan.
  *   count, dtype_size   message = count * dtype_size bytes; 0 is valid.
  *   root        absolute rank in [0, P).
@@ -111,7 +114,8 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
  * Run the whole broadcast [Sec. IV, listing: scatter, then ring]: launches the
  * plan's graph on hip_stream and returns without waiting (MPI's "blocking" is
  * the caller's stream synchronisation).  Every launch regenerates the tables
- * on the device and then executes all steps in order.
+ * on the device, executes the scatter levels in order and then the ring steps
+ * (see vbcast_set_ring_executor for the two ways the ring is run).
  * Errors: ARG (null), HIP.
  */
 int bcast_run(const vbcast_plan *plan, void *hip_stream);
@@ -132,6 +136,15 @@ int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stre
  */
 int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hip_stream,
                           float *step_ms);
+
+/*
+ * Run the whole broadcast once as plain launches (no graph) with events recorded
+ * on hip_stream between its three phases, wait, and write the elapsed
+ * milliseconds to phase_ms[0..2] (host array): table generation, scatter levels,
+ * ring phase (executed the way the plan's graph executes it).  Synchronous.
+ * Errors: ARG (null), HIP.
+ */
+int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms);
 
 typedef struct vbcast_plan_info {
     int32_t P, root, algo;
@@ -192,9 +205,30 @@ int bcast_plan_destroy(vbcast_plan *plan);
 
 /*
  * Copy-tile size used by plans created afterwards: a power of two between 4096
- * and 65536 bytes.  Process-wide; returns ARG for other values.
+ * and 65536 bytes (default 8192).  Process-wide; returns ARG for other values.
  */
 int vbcast_set_tile_bytes(size_t tile_bytes);
+
+/*
+ * How the graphs of plans created afterwards execute the P-1 ring steps
+ * [Sec. III-A: a rank forwards in step i+1 the chunk it received in step i]:
+ *   VBCAST_RING_STEPS   one copy kernel per ring step, in step order; every step
+ *                       is complete before the next starts.
+ *   VBCAST_RING_CHAINS  (default) one launch for the whole ring: every piece of
+ *                       every chunk is carried through its P-1 transfers in
+ *                       order, independently of the other pieces - the ordering
+ *                       MPI's blocking point-to-point calls impose, without a
+ *                       barrier between steps.  The same rows are copied, source
+ *                       to destination through memory, and the final state is
+ *                       the same; there is no global "state after step i" while
+ *                       it runs.
+ * bcast_run_steps always runs whole steps.  Process-wide; ARG for other values.
+ */
+int vbcast_set_ring_executor(int mode);
+
+/* Resident workgroups per compute unit for VBCAST_RING_CHAINS (1..16, default 2);
+ * together with the tile size this sets how many bytes are in flight at once. */
+int vbcast_set_chain_workgroups_per_cu(int k);
 
 /* Text for an error code; never NULL.  The pointer is valid until the calling
  * thread's next library call. */

@@ -14,7 +14,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvbcast.so")
-SOURCES = ["plan_kernels.hip", "copy_kernels.hip", "vbcast_api.hip"]
+SOURCES = ["plan_kernels.hip", "copy_kernels.hip", "chain_kernels.hip", "vbcast_api.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-result"]

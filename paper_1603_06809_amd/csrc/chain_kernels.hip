@@ -1,0 +1,174 @@
+// Ring phase executed in dependency order by one launch.
+//
+// In the ring a chunk travels: the chunk with relative index c starts at the
+// rank that holds it after the scatter and in ring step i is passed from
+// relative rank c + i - 1 to c + i [Sec. III-A: every rank forwards what it
+// received one step earlier].  So the transfer of a chunk in step i + 1 depends
+// only on that chunk's transfer in step i - never on another chunk - which is
+// all the ordering MPI's blocking calls impose; there is no barrier between
+// ring steps in the paper's code either [Sec. IV, listing].  The tuned ring
+// drops some transfers of a chain (the receiver already holds the chunk from
+// the scatter); the chain then continues from that receiver's copy.
+//
+// The message space [0, n) is cut into tile-aligned slabs.  A workgroup takes a
+// slab and walks it through all P - 1 ring steps: in step i it copies the slab's
+// part of each chunk from the step's source rank to its destination rank (the
+// same rows the step tables hold, looked up in the chunk-major "chain" view the
+// plan writes next to them), then fences and goes on with step i + 1, whose
+// source is what it has just written.  Every lane re-reads from memory exactly
+// the words it wrote one step earlier; the data is still in this XCD's L2, so
+// the only traffic that has to reach HBM is the write of every rank's copy.
+// The resident workgroups together hold (workgroups x tile) bytes in flight,
+// sized to stay inside the L2s; a workgroup that finishes a slab takes the next
+// one a whole grid further on, so all workgroups do the same amount of work.
+//
+// Between two steps a workgroup-scope fence orders the stores of one step
+// before the loads of the next.  Wider scopes are not needed and are costly
+// here: an agent-scope acquire invalidates the whole L2 of the XCD.
+
+#include "vbcast_internal.h"
+
+namespace vbcast {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Copy bytes [a, b) from src to dst (equal offsets, 16-byte aligned bases).
+template <int TILE_LOG2>
+__device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src,
+                                          uint8_t *__restrict__ dst, uint64_t a, uint64_t b) {
+    constexpr uint64_t TILE = 1ull << TILE_LOG2;
+    constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
+    const uint32_t tid = threadIdx.x;
+    if (b - a == TILE && (a & (TILE - 1)) == 0) {
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src + a);
+        u32x4 *d = reinterpret_cast<u32x4 *>(dst + a);
+        u32x4 v[PER_LANE];
+#pragma unroll
+        for (int k = 0; k < PER_LANE; ++k) v[k] = s[tid + k * kThreads];
+#pragma unroll
+        for (int k = 0; k < PER_LANE; ++k) d[tid + k * kThreads] = v[k];
+        return;
+    }
+    uint64_t body = (a + 15) & ~15ull;
+    if (body > b) body = b;
+    uint64_t tail = b & ~15ull;
+    if (tail < body) tail = body;
+    if (tid < (uint32_t)(body - a)) dst[a + tid] = src[a + tid];
+    if (tid >= 64 && tid - 64 < (uint32_t)(b - tail)) dst[tail + tid - 64] = src[tail + tid - 64];
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(src + body);
+    u32x4 *d = reinterpret_cast<u32x4 *>(dst + body);
+    const uint32_t words = (uint32_t)((tail - body) >> 4);
+    uint32_t w = tid;
+    for (; w + 3 * kThreads < words; w += 4 * kThreads) {
+        const u32x4 x0 = s[w], x1 = s[w + kThreads], x2 = s[w + 2 * kThreads],
+                    x3 = s[w + 3 * kThreads];
+        d[w] = x0;
+        d[w + kThreads] = x1;
+        d[w + 2 * kThreads] = x2;
+        d[w + 3 * kThreads] = x3;
+    }
+    for (; w < words; w += kThreads) d[w] = s[w];
+}
+
+__device__ __forceinline__ void step_fence() {
+    // Writer and reader of every byte are in the same workgroup (in fact the
+    // same lane), so workgroup scope is the right one: all wavefronts of a
+    // workgroup sit behind one L1, which their own stores keep consistent, and
+    // nothing has to be written back or invalidated - the fence only waits for
+    // the stores and keeps the next step's loads behind them.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+}
+
+// chain[c * (P - 1) + (i - 1)]: destination buffer of chunk c's transfer in ring
+// step i; bit 0 set = the step's table has no such row (dropped or empty).
+template <int TILE_LOG2>
+__global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restrict__ chain,
+                                                       const uint64_t *__restrict__ chunk_off,
+                                                       uint8_t *const *__restrict__ bases, int P,
+                                                       int root, uint64_t n, uint64_t ss,
+                                                       uint32_t n_slabs) {
+    constexpr uint64_t TILE = 1ull << TILE_LOG2;
+    const size_t hops = (size_t)P - 1;
+    for (uint32_t slab = blockIdx.x; slab < n_slabs; slab += gridDim.x) {
+        const uint64_t lo = (uint64_t)slab << TILE_LOG2;
+        const uint64_t hi = lo + TILE < n ? lo + TILE : n;
+        const int c0 = (int)(lo / ss);
+        const int c1 = (int)((hi - 1) / ss);
+        if (c1 - c0 <= 1) {
+            // one or two chunks meet in this slab: walk both chains together
+            const bool two = c1 > c0;
+            const uint64_t cut = two ? chunk_off[c1] : hi;
+            const uint64_t *chA = chain + (size_t)c0 * hops;
+            const uint64_t *chB = chain + (size_t)c1 * hops;
+            int rA = c0 + root;
+            if (rA >= P) rA -= P;
+            int rB = c1 + root;
+            if (rB >= P) rB -= P;
+            const uint8_t *srcA = bases[rA];
+            const uint8_t *srcB = bases[rB];
+            uint64_t eA = chA[0];
+            uint64_t eB = chB[0];
+            for (size_t i = 1; i <= hops; ++i) {
+                const size_t nx = i < hops ? i : 0;  // prefetch the next step's entries
+                const uint64_t nA = chA[nx];
+                const uint64_t nB = chB[nx];
+                uint8_t *dA = reinterpret_cast<uint8_t *>(eA & ~15ull);
+                uint8_t *dB = reinterpret_cast<uint8_t *>(eB & ~15ull);
+                if (!(eA & 1)) copy_span<TILE_LOG2>(srcA, dA, lo, cut);
+                if (two && !(eB & 1)) copy_span<TILE_LOG2>(srcB, dB, cut, hi);
+                step_fence();
+                srcA = dA;
+                srcB = dB;
+                eA = nA;
+                eB = nB;
+            }
+        } else {
+            // many small chunks in one slab (tiny messages): one chain after the other
+            for (int c = c0; c <= c1; ++c) {
+                const uint64_t a = chunk_off[c] > lo ? chunk_off[c] : lo;
+                const uint64_t b = chunk_off[c + 1] < hi ? chunk_off[c + 1] : hi;
+                if (a >= b) continue;
+                const uint64_t *ch = chain + (size_t)c * hops;
+                int r = c + root;
+                if (r >= P) r -= P;
+                const uint8_t *src = bases[r];
+                for (size_t i = 1; i <= hops; ++i) {
+                    const uint64_t e = ch[i - 1];
+                    uint8_t *d = reinterpret_cast<uint8_t *>(e & ~15ull);
+                    if (!(e & 1)) copy_span<TILE_LOG2>(src, d, a, b);
+                    step_fence();
+                    src = d;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t n_slabs, uint32_t grid,
+                             hipStream_t stream) {
+    if (n_slabs == 0 || pa.P < 2) return hipSuccess;
+    if (grid > n_slabs) grid = n_slabs;
+    if (grid == 0) grid = 1;
+    const dim3 g(grid), b(kThreads);
+#define VB_LAUNCH(TL)                                                                       \
+    hipLaunchKernelGGL(ring_chain<TL>, g, b, 0, stream, pa.chain, pa.chunk_off, pa.bases,   \
+                       pa.P, pa.root, pa.n, pa.ss, n_slabs)
+    switch (pa.tile_log2) {
+        case 12: VB_LAUNCH(12); break;
+        case 13: VB_LAUNCH(13); break;
+        case 14: VB_LAUNCH(14); break;
+        case 15: VB_LAUNCH(15); break;
+        case 16: VB_LAUNCH(16); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef VB_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace vbcast

@@ -148,7 +148,8 @@ __global__ __launch_bounds__(kThreads) void plan_descriptors(PlanArrays pa) {
 // its right neighbour.  NATIVE posts every such send.  TUNED posts it while
 // the sender's step <= P - i and afterwards only if the sender's tail is
 // send-only; the receiver decides symmetrically from its own (step, flag), and
-// the two decisions are compared (they always agree).
+// the two decisions are compared (they always agree).  Every ring decision is
+// also written into the chunk-major chain view used by the one-launch ring.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
     __shared__ uint32_t slots32[kWaves];
@@ -202,6 +203,15 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
             }
         }
         const bool valid = posted && len > 0;
+        if (!scatter && rho < P) {
+            // the same decision, filed under the chunk instead of the step
+            int c = rho + 1 - i;
+            if (c < 0) c += P;
+            int dst = dst_rel + pa.root;
+            if (dst >= P) dst -= P;
+            pa.chain[(size_t)c * (P - 1) + (i - 1)] =
+                reinterpret_cast<uint64_t>(pa.bases[dst]) | (valid ? 0ull : 1ull);
+        }
         uint32_t tiles_here = 0;
         if (valid) tiles_here = (uint32_t)(((off + len - 1) >> tl) - (off >> tl)) + 1u;
 

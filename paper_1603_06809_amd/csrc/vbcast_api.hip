@@ -31,6 +31,8 @@ struct vbcast_plan {
     // per-step counts, read back once at plan time
     std::vector<uint32_t> step_rows, step_tiles, step_posted, step_mismatch;
     std::vector<uint64_t> step_bytes;
+    int ring_executor = VBCAST_RING_CHAINS;  // what the graph uses for the ring phase
+    uint32_t chain_grid = 0;                 // workgroups of the one-launch ring
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
@@ -39,7 +41,9 @@ namespace {
 
 thread_local std::string g_hip_msg;
 thread_local std::string g_text;
-std::atomic<int> g_tile_log2{14};
+std::atomic<int> g_tile_log2{13};
+std::atomic<int> g_ring_executor{VBCAST_RING_CHAINS};
+std::atomic<int> g_chain_wgs_per_cu{2};
 
 int hip_fail(hipError_t e, const char *what) {
     g_hip_msg = std::string(what) + ": " + hipGetErrorString(e);
@@ -83,6 +87,20 @@ int launch_steps(const vbcast_plan *plan, int first, int last, hipStream_t strea
     return VBCAST_SUCCESS;
 }
 
+// The ring phase the way the plan's graph runs it.
+int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
+    const PlanArrays &pa = plan->pa;
+    if (pa.n_steps == 0) return VBCAST_SUCCESS;
+    if (plan->ring_executor == VBCAST_RING_CHAINS) {
+        const uint64_t tile = 1ull << pa.tile_log2;
+        const uint32_t n_slabs = (uint32_t)((pa.n + tile - 1) >> pa.tile_log2);
+        hipError_t e = vbcast::launch_ring_chain(pa, n_slabs, plan->chain_grid, stream);
+        if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
+        return VBCAST_SUCCESS;
+    }
+    return launch_steps(plan, pa.L, pa.n_steps, stream, nullptr);
+}
+
 int build_graph(vbcast_plan *plan) {
     hipStream_t cap = nullptr;
     HIP_TRY(hipStreamCreateWithFlags(&cap, hipStreamNonBlocking));
@@ -94,7 +112,9 @@ int build_graph(vbcast_plan *plan) {
     }
     e = vbcast::launch_plan_kernels(plan->pa, cap);
     if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
-    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, plan->pa.n_steps, cap, nullptr);
+    const PlanArrays &pa = plan->pa;
+    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, pa.n_steps ? pa.L : 0, cap, nullptr);
+    if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, cap);
     hipGraph_t graph = nullptr;
     e = hipStreamEndCapture(cap, &graph);
     (void)hipStreamDestroy(cap);
@@ -127,6 +147,18 @@ int vbcast_set_tile_bytes(size_t tile_bytes) {
             return VBCAST_SUCCESS;
         }
     return VBCAST_ERR_ARG;
+}
+
+int vbcast_set_ring_executor(int mode) {
+    if (mode != VBCAST_RING_STEPS && mode != VBCAST_RING_CHAINS) return VBCAST_ERR_ARG;
+    g_ring_executor.store(mode);
+    return VBCAST_SUCCESS;
+}
+
+int vbcast_set_chain_workgroups_per_cu(int k) {
+    if (k < 1 || k > 16) return VBCAST_ERR_ARG;
+    g_chain_wgs_per_cu.store(k);
+    return VBCAST_SUCCESS;
 }
 
 int vbcast_comm_create(int P, void *const *rank_bufs, size_t buf_bytes, vbcast_comm **out) {
@@ -203,6 +235,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     const size_t o_sw_step = lay.take(sizeof(int32_t) * Pz);
     const size_t o_sw_flag = lay.take(sizeof(int32_t) * Pz);
     const size_t o_rows = lay.take(sizeof(Row) * S * Pz);
+    const size_t o_chain = lay.take(sizeof(uint64_t) * Pz * (Pz - 1));
     const size_t o_tile_ptr = lay.take(sizeof(uint32_t) * S * (Pz + 1));
     const size_t o_tiles = lay.take(sizeof(Tile) * S * (size_t)pa.tile_cap);
     const size_t o_step_rows = lay.take(sizeof(uint32_t) * S);
@@ -229,6 +262,15 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     pa.sw_step = reinterpret_cast<int32_t *>(base + o_sw_step);
     pa.sw_flag = reinterpret_cast<int32_t *>(base + o_sw_flag);
     pa.rows = reinterpret_cast<Row *>(base + o_rows);
+    pa.chain = reinterpret_cast<uint64_t *>(base + o_chain);
+    pa.bases = comm->dev_bases;
+    plan->ring_executor = g_ring_executor.load();
+    {
+        int cus = 0;
+        hipError_t ce = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, comm->device);
+        if (ce != hipSuccess || cus < 1) cus = 256;
+        plan->chain_grid = (uint32_t)cus * (uint32_t)g_chain_wgs_per_cu.load();
+    }
     pa.tile_ptr = reinterpret_cast<uint32_t *>(base + o_tile_ptr);
     pa.tiles = reinterpret_cast<Tile *>(base + o_tiles);
     pa.step_rows = reinterpret_cast<uint32_t *>(base + o_step_rows);
@@ -319,6 +361,47 @@ int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hi
                 break;
             }
         }
+    }
+    for (auto &m : marks)
+        if (m) (void)hipEventDestroy(m);
+    return rc;
+}
+
+int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms) {
+    if (!plan || !phase_ms) return VBCAST_ERR_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t marks[4] = {nullptr, nullptr, nullptr, nullptr};
+    int rc = VBCAST_SUCCESS;
+    for (auto &m : marks) {
+        hipError_t e = hipEventCreate(&m);
+        if (e != hipSuccess) {
+            rc = hip_fail(e, "hipEventCreate");
+            break;
+        }
+    }
+    auto mark = [&](int k) {
+        if (rc != VBCAST_SUCCESS) return;
+        hipError_t e = hipEventRecord(marks[k], stream);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventRecord");
+    };
+    mark(0);
+    if (rc == VBCAST_SUCCESS) {
+        hipError_t e = vbcast::launch_plan_kernels(plan->pa, stream);
+        if (e != hipSuccess) rc = hip_fail(e, "plan kernels");
+    }
+    mark(1);
+    if (rc == VBCAST_SUCCESS)
+        rc = launch_steps(plan, 0, plan->pa.n_steps ? plan->pa.L : 0, stream, nullptr);
+    mark(2);
+    if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, stream);
+    mark(3);
+    if (rc == VBCAST_SUCCESS) {
+        hipError_t e = hipEventSynchronize(marks[3]);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventSynchronize");
+    }
+    for (int k = 0; k < 3 && rc == VBCAST_SUCCESS; ++k) {
+        hipError_t e = hipEventElapsedTime(&phase_ms[k], marks[k], marks[k + 1]);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventElapsedTime");
     }
     for (auto &m : marks)
         if (m) (void)hipEventDestroy(m);

@@ -38,7 +38,11 @@ struct PlanArrays {
     uint64_t *chunk_len;  // [P]
     int32_t *rel, *left, *right, *sw_step, *sw_flag;  // [P], by absolute rank
 
+    uint8_t *const *bases;  // [P] rank buffers, by absolute rank
+
     Row *rows;            // [n_steps][P]
+    uint64_t *chain;      // [P][P - 1] chunk-major view of the ring rows: destination
+                          // buffer of chunk c in ring step i, bit 0 set = no such row
     uint32_t *tile_ptr;   // [n_steps][P + 1] exclusive scan of tiles per row
     Tile *tiles;          // [n_steps][tile_cap]
 
@@ -55,5 +59,10 @@ hipError_t launch_plan_kernels(const PlanArrays &pa, hipStream_t stream);
 // Enqueue the copy kernel of one step; `n_tiles` > 0 workgroups.
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
                             uint32_t n_tiles, int tile_log2, hipStream_t stream);
+
+// Enqueue the ring phase as one launch that walks every slab of the message
+// through all ring steps; `grid` persistent workgroups share `n_slabs` slabs.
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t n_slabs, uint32_t grid,
+                             hipStream_t stream);
 
 }  // namespace vbcast

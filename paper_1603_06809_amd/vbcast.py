@@ -22,12 +22,16 @@ NATIVE = 0
 TUNED = 1
 ALGOS = {"native": NATIVE, "tuned": TUNED}
 
+RING_STEPS = 0
+RING_CHAINS = 1
+
 SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM = range(7)
 
 EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps",
-    "bcast_run_steps_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
-    "bcast_plan_export_tiles", "bcast_plan_destroy", "vbcast_set_tile_bytes", "bcast_strerror",
+    "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
+    "bcast_plan_export_tiles", "bcast_plan_destroy", "vbcast_set_tile_bytes",
+    "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "bcast_strerror",
 ]
 
 
@@ -73,12 +77,15 @@ def lib():
     L.bcast_run.argtypes = [vp, vp]
     L.bcast_run_steps.argtypes = [vp, C.c_int, C.c_int, vp]
     L.bcast_run_steps_timed.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_float)]
+    L.bcast_run_timed.argtypes = [vp, vp, C.POINTER(C.c_float)]
     L.bcast_plan_info.argtypes = [vp, C.POINTER(PlanInfo)]
     L.bcast_plan_export.argtypes = [vp, u64p, u32p, u32p, u64p, u64p, u64p]
     L.bcast_plan_export_desc.argtypes = [vp, u64p, u64p, i32p, i32p, i32p, i32p, i32p]
     L.bcast_plan_export_tiles.argtypes = [vp, C.c_int, u32p, u32p, u32p]
     L.bcast_plan_destroy.argtypes = [vp]
     L.vbcast_set_tile_bytes.argtypes = [C.c_size_t]
+    L.vbcast_set_ring_executor.argtypes = [C.c_int]
+    L.vbcast_set_chain_workgroups_per_cu.argtypes = [C.c_int]
     L.bcast_strerror.argtypes = [C.c_int]
     L.bcast_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -112,6 +119,14 @@ def _stream_handle(stream) -> Optional[int]:
 
 def vbcast_set_tile_bytes(tile_bytes: int) -> None:
     _check(lib().vbcast_set_tile_bytes(tile_bytes))
+
+
+def vbcast_set_ring_executor(mode: int) -> None:
+    _check(lib().vbcast_set_ring_executor(mode))
+
+
+def vbcast_set_chain_workgroups_per_cu(k: int) -> None:
+    _check(lib().vbcast_set_chain_workgroups_per_cu(k))
 
 
 class Comm:
@@ -176,6 +191,12 @@ class Plan:
         ms = np.zeros(max(last - first, 0), dtype=np.float32)
         _check(lib().bcast_run_steps_timed(self._h, first, last, _stream_handle(stream),
                                            _ptr(ms, C.c_float)))
+        return ms
+
+    def run_timed(self, stream=None) -> np.ndarray:
+        """One un-graphed run; milliseconds of (table generation, scatter, ring)."""
+        ms = np.zeros(3, dtype=np.float32)
+        _check(lib().bcast_run_timed(self._h, _stream_handle(stream), _ptr(ms, C.c_float)))
         return ms
 
     def export(self) -> Tables:

@@ -12,6 +12,7 @@ import harness as H
 pytestmark = pytest.mark.gpu
 
 ALGOS = [O.NATIVE, O.TUNED]
+DEFAULT_TILE = 8192
 
 
 @pytest.fixture(scope="module")
@@ -20,8 +21,16 @@ def V():
     assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_1603_06809_amd import vbcast
     vbcast.lib()
-    vbcast.vbcast_set_tile_bytes(1 << 14)
+    vbcast.vbcast_set_tile_bytes(DEFAULT_TILE)
+    vbcast.vbcast_set_ring_executor(vbcast.RING_CHAINS)
     return vbcast
+
+
+EXECUTORS = ["chains", "steps"]
+
+
+def set_executor(V, name):
+    V.vbcast_set_ring_executor(V.RING_CHAINS if name == "chains" else V.RING_STEPS)
 
 
 def sync():
@@ -29,10 +38,12 @@ def sync():
     torch.cuda.synchronize()
 
 
-def make(V, w, algo, pad=64):
+def make(V, w, algo, pad=64, executor="chains"):
     state = H.device_buffers(w, pad)
     comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
+    set_executor(V, executor)
     plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+    set_executor(V, "chains")
     return state, comm, plan
 
 
@@ -119,13 +130,18 @@ def test_edge_cases_every_step(V, algo):
             O.apply_step(ref, sched.steps[s])
             got = state.cpu().numpy()
             assert np.array_equal(got, np.stack(ref)), (P, root, n, algo, s)
-        # and the graph from a fresh state
-        H.refill(state, w)
-        plan.run()
-        sync()
-        want = O.broadcast_definition(H.host_buffers(w, pad=40), root, n)
-        assert np.array_equal(state.cpu().numpy(), np.stack(want)), (P, root, n, algo)
+        # and the graph from a fresh state, with either ring executor
+        want = np.stack(O.broadcast_definition(H.host_buffers(w, pad=40), root, n))
         plan.destroy()
+        for ex in EXECUTORS:
+            set_executor(V, ex)
+            plan = V.bcast_plan(comm, n, 1, root, algo)
+            set_executor(V, "chains")
+            H.refill(state, w)
+            plan.run()
+            sync()
+            assert np.array_equal(state.cpu().numpy(), want), (P, root, n, algo, ex)
+            plan.destroy()
         comm.destroy()
 
 
@@ -175,13 +191,15 @@ def test_state_at_sampled_steps(V, name, algo):
     comm.destroy()
 
 
+@pytest.mark.parametrize("executor", EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("name", ["P10_n512K", "P24_n4M", "P64_n16M", "P96_n12M_ragged"])
-def test_graph_run_final_state(V, name, algo):
+def test_graph_run_final_state(V, name, algo, executor):
     """bcast_run (the graph) from a fresh state, twice; the second launch
-    regenerates the tables and must give the same result."""
+    regenerates the tables and must give the same result.  Both ways of running
+    the ring phase."""
     w = I.workload(name)
-    state, comm, plan = make(V, w, algo)
+    state, comm, plan = make(V, w, algo, executor=executor)
     want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
     for _ in range(2):
         H.refill(state, w)
@@ -194,7 +212,7 @@ def test_graph_run_final_state(V, name, algo):
     comm.destroy()
 
 
-@pytest.mark.parametrize("tile", [4096, 8192, 32768, 65536])
+@pytest.mark.parametrize("tile", [4096, 16384, 32768, 65536])
 def test_other_tile_sizes(V, tile):
     w = I.workload("P24_n4M")
     V.vbcast_set_tile_bytes(tile)
@@ -202,6 +220,11 @@ def test_other_tile_sizes(V, tile):
         for algo in ALGOS:
             state, comm, plan = make(V, w, algo)
             assert plan.info().tile_bytes == tile
+            want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+            plan.run()          # the one-launch ring with this tile size
+            sync()
+            assert np.array_equal(state.cpu().numpy(), want)
+            H.refill(state, w)
             sched = O.build_schedule(w.P, w.root, w.n, algo)
             t = check_tables(plan, sched)
             check_tiles(plan, t, [0, sched.n_scatter_steps, sched.n_steps - 1])
@@ -214,7 +237,7 @@ def test_other_tile_sizes(V, tile):
             plan.destroy()
             comm.destroy()
     finally:
-        V.vbcast_set_tile_bytes(1 << 14)
+        V.vbcast_set_tile_bytes(DEFAULT_TILE)
 
 
 def test_timed_steps_report_a_time_per_step(V):
@@ -223,6 +246,10 @@ def test_timed_steps_report_a_time_per_step(V):
     ms = plan.run_steps_timed(0, plan.info().n_steps)
     assert ms.shape == (plan.info().n_steps,) and (ms > 0).all()
     want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+    assert np.array_equal(state.cpu().numpy(), want)
+    H.refill(state, w)
+    phases = plan.run_timed()
+    assert phases.shape == (3,) and (phases > 0).all()
     assert np.array_equal(state.cpu().numpy(), want)
     plan.destroy()
     comm.destroy()
@@ -308,15 +335,20 @@ def test_large_workload_state(V, big, algo):
         want = expected_rows(w, sched, stop, ranks, stride)
         for r in ranks:
             assert np.array_equal(state[r].cpu().numpy(), want[r]), (algo, stop, r)
-    # the whole broadcast through the graph, from a fresh state
-    H.refill(state, w)
-    V.bcast_run(plan)
-    sync()
-    msg = I.message_numpy(w)
-    for r in range(w.P):
-        got = state[r].cpu().numpy()
-        assert np.array_equal(got[: w.n], msg), (algo, r)
-        tail = H.host_tail(w, r, stride)
-        assert np.array_equal(got[w.n:], tail), (algo, r)
     plan.destroy()
+    # the whole broadcast through the graph, from a fresh state, with either ring executor
+    msg = I.message_numpy(w)
+    tails = [H.host_tail(w, r, stride) for r in range(w.P)]
+    for ex in EXECUTORS:
+        set_executor(V, ex)
+        plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+        set_executor(V, "chains")
+        H.refill(state, w)
+        V.bcast_run(plan)
+        sync()
+        for r in range(w.P):
+            got = state[r].cpu().numpy()
+            assert np.array_equal(got[: w.n], msg), (algo, ex, r)
+            assert np.array_equal(got[w.n:], tails[r]), (algo, ex, r)
+        plan.destroy()
     comm.destroy()
