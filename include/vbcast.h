@@ -74,7 +74,7 @@ enum {
 #define VBCAST_MAX_RANKS 8192
 
 /*
- * Create a communicator of P ranks [Sec. III-A: "P processes participating"].
+ * Create a communicator of P ranks [Sec. III-A: the P processes of the broadcast].
  *   rank_bufs  host array of P device pointers; rank r's buffer.  Every pointer
  *              must be 16-byte aligned so that a copy at equal offsets in two
  *              buffers is equally aligned on both sides.  Buffers must not

@@ -34,8 +34,6 @@ namespace {
 
 constexpr int kThreads = 256;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 // Copy bytes [a, b) from src to dst (equal offsets, 16-byte aligned bases).
 template <int TILE_LOG2>
 __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src,
@@ -44,8 +42,8 @@ __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src,
     constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
     const uint32_t tid = threadIdx.x;
     if (b - a == TILE && (a & (TILE - 1)) == 0) {
-        const u32x4 *s = reinterpret_cast<const u32x4 *>(src + a);
-        u32x4 *d = reinterpret_cast<u32x4 *>(dst + a);
+        const gmem_u32x4 *s = gmem_words(src + a);
+        gmem_u32x4 *d = gmem_words(dst + a);
         u32x4 v[PER_LANE];
 #pragma unroll
         for (int k = 0; k < PER_LANE; ++k) v[k] = s[tid + k * kThreads];
@@ -57,10 +55,12 @@ __device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src,
     if (body > b) body = b;
     uint64_t tail = b & ~15ull;
     if (tail < body) tail = body;
-    if (tid < (uint32_t)(body - a)) dst[a + tid] = src[a + tid];
-    if (tid >= 64 && tid - 64 < (uint32_t)(b - tail)) dst[tail + tid - 64] = src[tail + tid - 64];
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(src + body);
-    u32x4 *d = reinterpret_cast<u32x4 *>(dst + body);
+    const gmem_u8 *sb = gmem_bytes(src);
+    gmem_u8 *db = gmem_bytes(dst);
+    if (tid < (uint32_t)(body - a)) db[a + tid] = sb[a + tid];
+    if (tid >= 64 && tid - 64 < (uint32_t)(b - tail)) db[tail + tid - 64] = sb[tail + tid - 64];
+    const gmem_u32x4 *s = gmem_words(src + body);
+    gmem_u32x4 *d = gmem_words(dst + body);
     const uint32_t words = (uint32_t)((tail - body) >> 4);
     uint32_t w = tid;
     for (; w + 3 * kThreads < words; w += 4 * kThreads) {
@@ -93,12 +93,43 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
                                                        uint32_t n_slabs) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     const size_t hops = (size_t)P - 1;
-    for (uint32_t slab = blockIdx.x; slab < n_slabs; slab += gridDim.x) {
+    // Workgroups are handed to the XCDs round-robin (workgroup id mod 8).  Give
+    // each XCD one contiguous run of slabs per pass instead of every eighth slab,
+    // so that the addresses one XCD touches spread over all of its L2 channels.
+    const uint32_t W = gridDim.x;  // a multiple of 8
+    const uint32_t first = (blockIdx.x & 7u) * (W >> 3) + (blockIdx.x >> 3);
+    for (uint32_t slab = first; slab < n_slabs; slab += W) {
         const uint64_t lo = (uint64_t)slab << TILE_LOG2;
         const uint64_t hi = lo + TILE < n ? lo + TILE : n;
         const int c0 = (int)(lo / ss);
         const int c1 = (int)((hi - 1) / ss);
-        if (c1 - c0 <= 1) {
+        if (c1 == c0 && hi - lo == TILE) {
+            // The common case, a whole tile inside one chunk: every lane owns the
+            // same PER_LANE words in every step, only the two buffers change.
+            constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
+            const uint32_t lane_off = threadIdx.x * 16u;
+            const uint64_t *ch = chain + (size_t)c0 * hops;
+            int r = c0 + root;
+            if (r >= P) r -= P;
+            const uint8_t *src = bases[r] + lo;
+            uint64_t e = ch[0];
+            for (size_t i = 1; i <= hops; ++i) {
+                const uint64_t nxt = ch[i < hops ? i : 0];  // next step's entry, early
+                uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull) + lo;
+                if (!(e & 1)) {
+                    u32x4 v[PER_LANE];
+#pragma unroll
+                    for (int k = 0; k < PER_LANE; ++k)
+                        v[k] = *gmem_words(src + lane_off + k * (kThreads * 16));
+#pragma unroll
+                    for (int k = 0; k < PER_LANE; ++k)
+                        *gmem_words(dst + lane_off + k * (kThreads * 16)) = v[k];
+                }
+                step_fence();
+                src = dst;
+                e = nxt;
+            }
+        } else if (c1 - c0 <= 1) {
             // one or two chunks meet in this slab: walk both chains together
             const bool two = c1 > c0;
             const uint64_t cut = two ? chunk_off[c1] : hi;
@@ -154,7 +185,7 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t n_slabs, uint32_t gr
                              hipStream_t stream) {
     if (n_slabs == 0 || pa.P < 2) return hipSuccess;
     if (grid > n_slabs) grid = n_slabs;
-    if (grid == 0) grid = 1;
+    grid = (grid + 7u) & ~7u;  // whole rounds over the 8 XCDs
     const dim3 g(grid), b(kThreads);
 #define VB_LAUNCH(TL)                                                                       \
     hipLaunchKernelGGL(ring_chain<TL>, g, b, 0, stream, pa.chain, pa.chunk_off, pa.bases,   \

@@ -20,18 +20,23 @@ namespace {
 
 constexpr int kThreads = 256;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 template <int TILE_LOG2>
 __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ rows,
                                                       const Tile *__restrict__ tiles,
-                                                      uint8_t *const *__restrict__ bases) {
+                                                      uint8_t *const *__restrict__ bases,
+                                                      uint32_t n_tiles) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     constexpr int WORDS = (int)(TILE / 16);      // 16-byte words in a full tile
     constexpr int PER_LANE = WORDS / kThreads;   // words per lane in a full tile
     static_assert(PER_LANE >= 1, "tile too small for the workgroup");
 
-    const Tile t = tiles[blockIdx.x];
+    // Workgroups go to the XCDs round-robin (workgroup id mod 8): give each XCD a
+    // contiguous eighth of the step's tiles rather than every eighth tile, so
+    // that its addresses spread over all of its L2 channels.
+    const uint32_t per_xcd = gridDim.x >> 3;  // the grid is a multiple of 8
+    const uint32_t tile_id = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (tile_id >= n_tiles) return;
+    const Tile t = tiles[tile_id];
     const Row r = rows[t.row];
     const uint8_t *__restrict__ src = bases[r.src];
     uint8_t *__restrict__ dst = bases[r.dst];
@@ -44,8 +49,8 @@ __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ ro
     const uint32_t tid = threadIdx.x;
 
     if (hi - lo == TILE) {  // whole aligned window
-        const u32x4 *s = reinterpret_cast<const u32x4 *>(src + lo);
-        u32x4 *d = reinterpret_cast<u32x4 *>(dst + lo);
+        const gmem_u32x4 *s = gmem_words(src + lo);
+        gmem_u32x4 *d = gmem_words(dst + lo);
         u32x4 v[PER_LANE];
 #pragma unroll
         for (int k = 0; k < PER_LANE; ++k) v[k] = s[tid + k * kThreads];
@@ -61,11 +66,13 @@ __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ ro
     uint64_t tail = hi & ~15ull;
     if (tail < body) tail = body;
 
-    if (tid < (uint32_t)(body - lo)) dst[lo + tid] = src[lo + tid];
-    if (tid >= 64 && tid - 64 < (uint32_t)(hi - tail)) dst[tail + tid - 64] = src[tail + tid - 64];
+    const gmem_u8 *sb = gmem_bytes(src);
+    gmem_u8 *db = gmem_bytes(dst);
+    if (tid < (uint32_t)(body - lo)) db[lo + tid] = sb[lo + tid];
+    if (tid >= 64 && tid - 64 < (uint32_t)(hi - tail)) db[tail + tid - 64] = sb[tail + tid - 64];
 
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(src + body);
-    u32x4 *d = reinterpret_cast<u32x4 *>(dst + body);
+    const gmem_u32x4 *s = gmem_words(src + body);
+    gmem_u32x4 *d = gmem_words(dst + body);
     const uint32_t words = (uint32_t)((tail - body) >> 4);
     uint32_t w = tid;
     for (; w + 3 * kThreads < words; w += 4 * kThreads) {
@@ -82,13 +89,13 @@ __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ ro
 
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
                             uint32_t n_tiles, int tile_log2, hipStream_t stream) {
-    const dim3 grid(n_tiles), block(kThreads);
+    const dim3 grid((n_tiles + 7u) & ~7u), block(kThreads);
     switch (tile_log2) {
-        case 12: hipLaunchKernelGGL(step_copy<12>, grid, block, 0, stream, rows, tiles, bases); break;
-        case 13: hipLaunchKernelGGL(step_copy<13>, grid, block, 0, stream, rows, tiles, bases); break;
-        case 14: hipLaunchKernelGGL(step_copy<14>, grid, block, 0, stream, rows, tiles, bases); break;
-        case 15: hipLaunchKernelGGL(step_copy<15>, grid, block, 0, stream, rows, tiles, bases); break;
-        case 16: hipLaunchKernelGGL(step_copy<16>, grid, block, 0, stream, rows, tiles, bases); break;
+        case 12: hipLaunchKernelGGL(step_copy<12>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
+        case 13: hipLaunchKernelGGL(step_copy<13>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
+        case 14: hipLaunchKernelGGL(step_copy<14>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
+        case 15: hipLaunchKernelGGL(step_copy<15>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
+        case 16: hipLaunchKernelGGL(step_copy<16>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kThreads) void plan_tiles(PlanArrays pa) {
 
 }  // namespace
 
-hipError_t launch_plan_kernels(const PlanArrays &pa, hipStream_t stream) {
+hipError_t launch_plan_kernels(const PlanArrays &pa, int tile_map_steps, hipStream_t stream) {
     hipLaunchKernelGGL(plan_descriptors, dim3(1), dim3(kThreads), 0, stream, pa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -297,8 +297,10 @@ hipError_t launch_plan_kernels(const PlanArrays &pa, hipStream_t stream) {
     hipLaunchKernelGGL(plan_rows, dim3(pa.n_steps), dim3(kThreads), 0, stream, pa);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (tile_map_steps <= 0) return hipSuccess;
+    if (tile_map_steps > pa.n_steps) tile_map_steps = pa.n_steps;
     const uint32_t gx = (pa.tile_cap + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(plan_tiles, dim3(gx, pa.n_steps), dim3(kThreads), 0, stream, pa);
+    hipLaunchKernelGGL(plan_tiles, dim3(gx, tile_map_steps), dim3(kThreads), 0, stream, pa);
     return hipGetLastError();
 }
 

@@ -101,6 +101,12 @@ int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     return launch_steps(plan, pa.L, pa.n_steps, stream, nullptr);
 }
 
+int graph_tile_map_steps(const vbcast_plan *plan) {
+    const PlanArrays &pa = plan->pa;
+    if (pa.n_steps == 0) return 0;
+    return plan->ring_executor == VBCAST_RING_CHAINS ? pa.L : pa.n_steps;
+}
+
 int build_graph(vbcast_plan *plan) {
     hipStream_t cap = nullptr;
     HIP_TRY(hipStreamCreateWithFlags(&cap, hipStreamNonBlocking));
@@ -110,9 +116,11 @@ int build_graph(vbcast_plan *plan) {
         (void)hipStreamDestroy(cap);
         return hip_fail(e, "hipStreamBeginCapture");
     }
-    e = vbcast::launch_plan_kernels(plan->pa, cap);
-    if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
     const PlanArrays &pa = plan->pa;
+    // The one-launch ring reads the chain view, not tile maps: inside the graph
+    // only the scatter levels need theirs rebuilt.
+    e = vbcast::launch_plan_kernels(pa, graph_tile_map_steps(plan), cap);
+    if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
     if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, pa.n_steps ? pa.L : 0, cap, nullptr);
     if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, cap);
     hipGraph_t graph = nullptr;
@@ -280,7 +288,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     pa.step_bytes = reinterpret_cast<uint64_t *>(base + o_step_bytes);
 
     int rc = VBCAST_SUCCESS;
-    e = vbcast::launch_plan_kernels(pa, stream);
+    e = vbcast::launch_plan_kernels(pa, pa.n_steps, stream);
     if (e != hipSuccess) rc = hip_fail(e, "plan kernels");
 
     plan->step_rows.resize(S);
@@ -386,7 +394,7 @@ int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms) 
     };
     mark(0);
     if (rc == VBCAST_SUCCESS) {
-        hipError_t e = vbcast::launch_plan_kernels(plan->pa, stream);
+        hipError_t e = vbcast::launch_plan_kernels(plan->pa, graph_tile_map_steps(plan), stream);
         if (e != hipSuccess) rc = hip_fail(e, "plan kernels");
     }
     mark(1);

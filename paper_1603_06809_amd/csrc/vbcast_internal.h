@@ -53,8 +53,27 @@ struct PlanArrays {
     uint64_t *step_bytes;   // [n_steps]
 };
 
-// Enqueue the three generation kernels (descriptors, rows, tile maps).
-hipError_t launch_plan_kernels(const PlanArrays &pa, hipStream_t stream);
+// Rank buffers are ordinary device allocations.  Pointers that come out of a
+// table are generic to the compiler; these types put them back into the global
+// address space so that copies compile to global (not flat) memory instructions.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) u32x4 gmem_u32x4;
+typedef __attribute__((address_space(1))) uint8_t gmem_u8;
+
+__device__ __forceinline__ const gmem_u32x4 *gmem_words(const uint8_t *p) {
+    return (const gmem_u32x4 *)(uintptr_t)p;
+}
+__device__ __forceinline__ gmem_u32x4 *gmem_words(uint8_t *p) {
+    return (gmem_u32x4 *)(uintptr_t)p;
+}
+__device__ __forceinline__ const gmem_u8 *gmem_bytes(const uint8_t *p) {
+    return (const gmem_u8 *)(uintptr_t)p;
+}
+__device__ __forceinline__ gmem_u8 *gmem_bytes(uint8_t *p) { return (gmem_u8 *)(uintptr_t)p; }
+
+// Enqueue the three generation kernels (descriptors, rows, tile maps); tile maps
+// are (re)built for the first `tile_map_steps` steps only.
+hipError_t launch_plan_kernels(const PlanArrays &pa, int tile_map_steps, hipStream_t stream);
 
 // Enqueue the copy kernel of one step; `n_tiles` > 0 workgroups.
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,

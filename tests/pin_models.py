@@ -4,7 +4,7 @@ are used to pin it.  Neither imports the oracle.
 1. ``prose_model``: the broadcast as the paper *describes* it in words, on sets
    of chunk numbers: a binomial tree built by recursive halving, a ring in
    which every rank forwards what it got one step earlier, and - for the tuned
-   variant - "each process only receives those missing data chunks"
+   variant - a transfer happens only if the receiver still lacks the chunk
    [Sec. III-A, Sec. IV prose and Figs. 1-5].  No mask loop, no step/flag.
 
 2. ``MailboxWorld``: an asynchronous execution of P per-rank programs that

@@ -198,7 +198,7 @@ def test_tuned_saving_power_of_two(k):
 
 @pytest.mark.parametrize("P", range(1, 41))
 def test_tuned_rule_equals_only_missing_chunks(P):
-    """Sec. IV: 'each process only receives those missing data chunks'.  The
+    """Sec. IV: a rank receives a chunk only if it still lacks it.  The
     (step, flag) rule must drop exactly the transfers whose receiver already
     holds the chunk, in every step, for every root."""
     for tuned in (False, True):
