@@ -92,24 +92,28 @@ def main() -> int:
         V.vbcast_set_chain_workgroups_per_cu(args.chain_wgs_per_cu)
     V.vbcast_set_ring_executor(V.RING_CHAINS if args.ring_executor == "chains" else V.RING_STEPS)
 
-    w = I.workload(args.workload)
-    stride = (w.n + args.pad + 255) // 256 * 256
     def say(text):
         print(f"[bench] {text}", file=sys.stderr, flush=True)
 
-    say(f"allocating {w.P} x {stride} bytes")
-    state = torch.empty((w.P, stride), dtype=torch.uint8, device="cuda")
+    w = I.workload(args.workload)
+    stride = (w.n + args.pad + 255) // 256 * 256
+    # One allocation per rank, as P processes would have: besides being the
+    # natural layout it is the robust one - a single 64 GiB block is placed by the
+    # driver in ways that make the same kernel 15 % slower on most runs.
+    say(f"allocating {w.P} rank buffers of {stride} bytes")
+    bufs = [torch.empty(stride, dtype=torch.uint8, device="cuda") for _ in range(w.P)]
     msg = I.message_torch(w, "cuda")
     if args.init == "fast":
         torch.manual_seed(w.seed)
-        state.view(torch.int64).random_()
+        for b in bufs:
+            b.view(torch.int64).random_()
     else:
-        for r in range(w.P):
-            state[r].copy_(I.poison_torch(w, r, stride, "cuda"))
-    state[w.root, : w.n].copy_(msg)
+        for r, b in enumerate(bufs):
+            b.copy_(I.poison_torch(w, r, stride, "cuda"))
+    bufs[w.root][: w.n].copy_(msg)
     torch.cuda.synchronize()
     say("buffers filled")
-    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], stride)
+    comm = V.Comm([b.data_ptr() for b in bufs], stride)
 
     stream = torch.cuda.current_stream()
     results = {}
@@ -141,7 +145,7 @@ def main() -> int:
         }
 
     # correctness of what was timed: every rank now holds the message
-    ok = all(bool(torch.equal(state[r, : w.n], msg)) for r in range(w.P))
+    ok = all(bool(torch.equal(b[: w.n], msg)) for b in bufs)
 
     say(f"result check: {ok}")
     # per-launch timing of the dominant kernel (the ring phase), tuned plan, with
@@ -212,7 +216,7 @@ def main() -> int:
     for p in plans.values():
         p.destroy()
     comm.destroy()
-    del state
+    del bufs
     torch.cuda.empty_cache()
     if not args.no_cpu:
         say("timing the CPU oracle on the bounded sample")

@@ -130,9 +130,15 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
                 e = nxt;
             }
         } else if (c1 - c0 <= 1) {
-            // one or two chunks meet in this slab: walk both chains together
-            const bool two = c1 > c0;
-            const uint64_t cut = two ? chunk_off[c1] : hi;
+            // One or two chunks meet in this slab (or the message ends in it).  The
+            // slab is still a row of 16-byte words at fixed places: a lane keeps its
+            // PER_LANE words and only picks, per word, which of the two chains the
+            // word belongs to.  The word that holds the cut between the chunks and
+            // the word that holds the end of the message go byte by byte, one lane
+            // per byte (lanes 0-15 and 16-31).
+            constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
+            const uint32_t tid = threadIdx.x;
+            const uint64_t cut = c1 > c0 ? chunk_off[c1] : hi;   // A = [lo, cut), B = [cut, hi)
             const uint64_t *chA = chain + (size_t)c0 * hops;
             const uint64_t *chB = chain + (size_t)c1 * hops;
             int rA = c0 + root;
@@ -141,16 +147,49 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
             if (rB >= P) rB -= P;
             const uint8_t *srcA = bases[rA];
             const uint8_t *srcB = bases[rB];
+
+            uint64_t word_at[PER_LANE];
+            bool word_a[PER_LANE], word_b[PER_LANE];
+#pragma unroll
+            for (int k = 0; k < PER_LANE; ++k) {
+                word_at[k] = lo + (uint64_t)(tid + k * kThreads) * 16u;
+                word_a[k] = word_at[k] + 16 <= cut;
+                word_b[k] = word_at[k] >= cut && word_at[k] + 16 <= hi;
+            }
+            // byte lanes: lanes 0-15 take the word holding `cut`, 16-31 the word holding `hi`
+            const uint64_t byte_at = (tid < 16 ? (cut & ~15ull) : (hi & ~15ull)) + (tid & 15u);
+            const bool byte_lane = tid < 32 && byte_at >= lo && byte_at < hi &&
+                                   (tid < 16 ? (cut & 15u) != 0
+                                             : ((hi & 15u) != 0 && (hi & ~15ull) != (cut & ~15ull)));
+            const bool byte_a = byte_lane && byte_at < cut;
+            const bool byte_b = byte_lane && byte_at >= cut;
+
             uint64_t eA = chA[0];
             uint64_t eB = chB[0];
             for (size_t i = 1; i <= hops; ++i) {
-                const size_t nx = i < hops ? i : 0;  // prefetch the next step's entries
+                const size_t nx = i < hops ? i : 0;  // the next step's entries, early
                 const uint64_t nA = chA[nx];
                 const uint64_t nB = chB[nx];
                 uint8_t *dA = reinterpret_cast<uint8_t *>(eA & ~15ull);
                 uint8_t *dB = reinterpret_cast<uint8_t *>(eB & ~15ull);
-                if (!(eA & 1)) copy_span<TILE_LOG2>(srcA, dA, lo, cut);
-                if (two && !(eB & 1)) copy_span<TILE_LOG2>(srcB, dB, cut, hi);
+                const bool runA = !(eA & 1), runB = !(eB & 1);
+                u32x4 v[PER_LANE];
+                bool on[PER_LANE];
+#pragma unroll
+                for (int k = 0; k < PER_LANE; ++k) {
+                    on[k] = (word_a[k] && runA) || (word_b[k] && runB);
+                    const uint8_t *s = word_a[k] ? srcA : srcB;
+                    if (on[k]) v[k] = *gmem_words(s + word_at[k]);
+                }
+                const bool byte_on = (byte_a && runA) || (byte_b && runB);
+                uint8_t one = 0;
+                if (byte_on) one = *gmem_bytes((byte_a ? srcA : srcB) + byte_at);
+#pragma unroll
+                for (int k = 0; k < PER_LANE; ++k) {
+                    uint8_t *d = word_a[k] ? dA : dB;
+                    if (on[k]) *gmem_words(d + word_at[k]) = v[k];
+                }
+                if (byte_on) *gmem_bytes((byte_a ? dA : dB) + byte_at) = one;
                 step_fence();
                 srcA = dA;
                 srcB = dB;
