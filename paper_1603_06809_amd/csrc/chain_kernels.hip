@@ -10,7 +10,8 @@
 // drops some transfers of a chain (the receiver already holds the chunk from
 // the scatter); the chain then continues from that receiver's copy.
 //
-// The message space [0, n) is cut into tile-aligned slabs.  A workgroup takes a
+// (Chunks at least a tile long; shorter chunks take the per-wavefront kernel at
+// the end of this file.)  The message space [0, n) is cut into tile-aligned slabs.  A workgroup takes a
 // slab and walks it through all P - 1 ring steps: in step i it copies the slab's
 // part of each chunk from the step's source rank to its destination rank (the
 // same rows the step tables hold, looked up in the chunk-major "chain" view the
@@ -33,46 +34,6 @@ namespace vbcast {
 namespace {
 
 constexpr int kThreads = 256;
-
-// Copy bytes [a, b) from src to dst (equal offsets, 16-byte aligned bases).
-template <int TILE_LOG2>
-__device__ __forceinline__ void copy_span(const uint8_t *__restrict__ src,
-                                          uint8_t *__restrict__ dst, uint64_t a, uint64_t b) {
-    constexpr uint64_t TILE = 1ull << TILE_LOG2;
-    constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
-    const uint32_t tid = threadIdx.x;
-    if (b - a == TILE && (a & (TILE - 1)) == 0) {
-        const gmem_u32x4 *s = gmem_words(src + a);
-        gmem_u32x4 *d = gmem_words(dst + a);
-        u32x4 v[PER_LANE];
-#pragma unroll
-        for (int k = 0; k < PER_LANE; ++k) v[k] = s[tid + k * kThreads];
-#pragma unroll
-        for (int k = 0; k < PER_LANE; ++k) d[tid + k * kThreads] = v[k];
-        return;
-    }
-    uint64_t body = (a + 15) & ~15ull;
-    if (body > b) body = b;
-    uint64_t tail = b & ~15ull;
-    if (tail < body) tail = body;
-    const gmem_u8 *sb = gmem_bytes(src);
-    gmem_u8 *db = gmem_bytes(dst);
-    if (tid < (uint32_t)(body - a)) db[a + tid] = sb[a + tid];
-    if (tid >= 64 && tid - 64 < (uint32_t)(b - tail)) db[tail + tid - 64] = sb[tail + tid - 64];
-    const gmem_u32x4 *s = gmem_words(src + body);
-    gmem_u32x4 *d = gmem_words(dst + body);
-    const uint32_t words = (uint32_t)((tail - body) >> 4);
-    uint32_t w = tid;
-    for (; w + 3 * kThreads < words; w += 4 * kThreads) {
-        const u32x4 x0 = s[w], x1 = s[w + kThreads], x2 = s[w + 2 * kThreads],
-                    x3 = s[w + 3 * kThreads];
-        d[w] = x0;
-        d[w + kThreads] = x1;
-        d[w + 2 * kThreads] = x2;
-        d[w + 3 * kThreads] = x3;
-    }
-    for (; w < words; w += kThreads) d[w] = s[w];
-}
 
 __device__ __forceinline__ void step_fence() {
     // Writer and reader of every byte are in the same workgroup (in fact the
@@ -129,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
                 src = dst;
                 e = nxt;
             }
-        } else if (c1 - c0 <= 1) {
+        } else {
             // One or two chunks meet in this slab (or the message ends in it).  The
             // slab is still a row of 16-byte words at fixed places: a lane keeps its
             // PER_LANE words and only picks, per word, which of the two chains the
@@ -196,25 +157,61 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
                 eA = nA;
                 eB = nB;
             }
-        } else {
-            // many small chunks in one slab (tiny messages): one chain after the other
-            for (int c = c0; c <= c1; ++c) {
-                const uint64_t a = chunk_off[c] > lo ? chunk_off[c] : lo;
-                const uint64_t b = chunk_off[c + 1] < hi ? chunk_off[c + 1] : hi;
-                if (a >= b) continue;
-                const uint64_t *ch = chain + (size_t)c * hops;
-                int r = c + root;
-                if (r >= P) r -= P;
-                const uint8_t *src = bases[r];
-                for (size_t i = 1; i <= hops; ++i) {
-                    const uint64_t e = ch[i - 1];
-                    uint8_t *d = reinterpret_cast<uint8_t *>(e & ~15ull);
-                    if (!(e & 1)) copy_span<TILE_LOG2>(src, d, a, b);
-                    step_fence();
-                    src = d;
-                }
-            }
         }
+    }
+}
+
+// Small chunks (chunk size below the tile size): one wavefront per chunk.  A
+// wavefront walks its whole chunk through the P - 1 steps on its own; the four
+// wavefronts of a workgroup are independent.  Lanes 0-15 take the bytes before
+// the first 16-byte boundary, lanes 16-31 the bytes after the last one, and all
+// lanes share the 16-byte words in between, four words per lane in flight.
+__global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__restrict__ chain,
+                                                             const uint64_t *__restrict__ chunk_off,
+                                                             uint8_t *const *__restrict__ bases,
+                                                             int P, int root) {
+    const size_t hops = (size_t)P - 1;
+    const int c = (int)(blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6));
+    if (c >= P) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t a = chunk_off[c], b = chunk_off[c + 1];
+    if (a >= b) return;
+    uint64_t body = (a + 15) & ~15ull;
+    if (body > b) body = b;
+    uint64_t tail = b & ~15ull;
+    if (tail < body) tail = body;
+    const bool head_lane = lane < 16 && lane < (uint32_t)(body - a);
+    const bool tail_lane = lane >= 16 && lane < 32 && lane - 16 < (uint32_t)(b - tail);
+    const uint64_t byte_at = head_lane ? a + lane : tail + (lane - 16);
+    const uint32_t words = (uint32_t)((tail - body) >> 4);
+
+    const uint64_t *ch = chain + (size_t)c * hops;
+    int r = c + root;
+    if (r >= P) r -= P;
+    const uint8_t *src = bases[r];
+    uint64_t e = ch[0];
+    for (size_t i = 1; i <= hops; ++i) {
+        const uint64_t nxt = ch[i < hops ? i : 0];
+        uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull);
+        if (!(e & 1)) {
+            uint8_t one = 0;
+            if (head_lane || tail_lane) one = *gmem_bytes(src + byte_at);
+            const gmem_u32x4 *s = gmem_words(src + body);
+            gmem_u32x4 *d = gmem_words(dst + body);
+            uint32_t w = lane;
+            for (; w + 192 < words; w += 256) {
+                const u32x4 x0 = s[w], x1 = s[w + 64], x2 = s[w + 128], x3 = s[w + 192];
+                d[w] = x0;
+                d[w + 64] = x1;
+                d[w + 128] = x2;
+                d[w + 192] = x3;
+            }
+            for (; w < words; w += 64) d[w] = s[w];
+            if (head_lane || tail_lane) *gmem_bytes(dst + byte_at) = one;
+        }
+        step_fence();
+        src = dst;
+        e = nxt;
     }
 }
 
@@ -223,6 +220,14 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t n_slabs, uint32_t grid,
                              hipStream_t stream) {
     if (n_slabs == 0 || pa.P < 2) return hipSuccess;
+    if (pa.ss < (1ull << pa.tile_log2)) {
+        // chunks smaller than a tile: one wavefront per chunk
+        const uint32_t per_wg = kThreads / 64;
+        hipLaunchKernelGGL(ring_chain_small, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
+                           dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P,
+                           pa.root);
+        return hipGetLastError();
+    }
     if (grid > n_slabs) grid = n_slabs;
     grid = (grid + 7u) & ~7u;  // whole rounds over the 8 XCDs
     const dim3 g(grid), b(kThreads);

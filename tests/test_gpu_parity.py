@@ -274,6 +274,41 @@ def test_errors_on_device(V):
     comm.destroy()
 
 
+# ------------------------------------------------------------------ the paper's own shapes
+
+PAPER_SHAPES = (
+    [(P, n) for P in (9, 17, 33, 65, 129) for n in (12_288, 524_287, 1_048_576)]   # Sec. V-B
+    + [(129, 2_560_000)]
+    + [(16, 524_288), (16, 30_000_000), (64, 3_000_000), (64, 30_000_000),       # Sec. V-A
+       (256, 524_288), (256, 3_000_000)]
+)
+
+
+@pytest.mark.parametrize("P,n", PAPER_SHAPES)
+def test_paper_sweep_shapes(V, P, n):
+    """Process counts and message sizes of the paper's experiments (Sec. V):
+    tables exact, final state exact, both schedules, both ring executors."""
+    w = I.Workload(f"paper_P{P}_n{n}", P, P // 3, n, seed=77_000 + P)
+    init = H.host_buffers(w)
+    want = np.stack(O.broadcast_definition(init, w.root, w.n))
+    state = H.device_buffers(w)
+    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
+    for algo in ALGOS:
+        sched = O.build_schedule(P, w.root, n, algo)
+        for ex in EXECUTORS:
+            set_executor(V, ex)
+            plan = V.bcast_plan(comm, n, 1, w.root, algo)
+            set_executor(V, "chains")
+            if ex == "chains":
+                check_tables(plan, sched)
+            H.refill(state, w)
+            V.bcast_run(plan)
+            sync()
+            assert np.array_equal(state.cpu().numpy(), want), (P, n, algo, ex)
+            plan.destroy()
+    comm.destroy()
+
+
 # ------------------------------------------------------------------ the large workload
 
 @pytest.fixture(scope="module")
