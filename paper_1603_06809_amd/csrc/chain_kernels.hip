@@ -161,19 +161,21 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
     }
 }
 
-// Small chunks (chunk size below the tile size): one wavefront per chunk.  A
-// wavefront walks its whole chunk through the P - 1 steps on its own; the four
-// wavefronts of a workgroup are independent.  Lanes 0-15 take the bytes before
-// the first 16-byte boundary, lanes 16-31 the bytes after the last one, and all
-// lanes share the 16-byte words in between, four words per lane in flight.
+// Small chunks (shorter than the smallest slab): a group of LANES lanes - one
+// wavefront, or the whole workgroup for chunks above 1 KiB - walks a whole chunk
+// through the P - 1 steps.  Groups, and the wavefronts inside a group, are
+// independent: a lane only ever re-reads what it wrote itself.  Lanes 0-15 take
+// the bytes before the first 16-byte boundary, lanes 16-31 the bytes after the
+// last one, and all lanes share the 16-byte words in between.
+template <int LANES>
 __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__restrict__ chain,
                                                              const uint64_t *__restrict__ chunk_off,
                                                              uint8_t *const *__restrict__ bases,
                                                              int P, int root) {
     const size_t hops = (size_t)P - 1;
-    const int c = (int)(blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6));
+    const int c = (int)(blockIdx.x * (kThreads / LANES) + (threadIdx.x / LANES));
     if (c >= P) return;
-    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t lane = threadIdx.x % LANES;
     const uint64_t a = chunk_off[c], b = chunk_off[c + 1];
     if (a >= b) return;
     uint64_t body = (a + 15) & ~15ull;
@@ -199,14 +201,15 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
             const gmem_u32x4 *s = gmem_words(src + body);
             gmem_u32x4 *d = gmem_words(dst + body);
             uint32_t w = lane;
-            for (; w + 192 < words; w += 256) {
-                const u32x4 x0 = s[w], x1 = s[w + 64], x2 = s[w + 128], x3 = s[w + 192];
+            for (; w + 3 * LANES < words; w += 4 * LANES) {
+                const u32x4 x0 = s[w], x1 = s[w + LANES], x2 = s[w + 2 * LANES],
+                            x3 = s[w + 3 * LANES];
                 d[w] = x0;
-                d[w + 64] = x1;
-                d[w + 128] = x2;
-                d[w + 192] = x3;
+                d[w + LANES] = x1;
+                d[w + 2 * LANES] = x2;
+                d[w + 3 * LANES] = x3;
             }
-            for (; w < words; w += 64) d[w] = s[w];
+            for (; w < words; w += LANES) d[w] = s[w];
             if (head_lane || tail_lane) *gmem_bytes(dst + byte_at) = one;
         }
         step_fence();
@@ -217,24 +220,40 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
 
 }  // namespace
 
-hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t n_slabs, uint32_t grid,
-                             hipStream_t stream) {
-    if (n_slabs == 0 || pa.P < 2) return hipSuccess;
-    if (pa.ss < (1ull << pa.tile_log2)) {
-        // chunks smaller than a tile: one wavefront per chunk
-        const uint32_t per_wg = kThreads / 64;
-        hipLaunchKernelGGL(ring_chain_small, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
-                           dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P,
-                           pa.root);
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream) {
+    if (pa.n == 0 || pa.P < 2) return hipSuccess;
+    // Slab size: the plan's tile, halved until a slab cannot hold more than one
+    // chunk boundary (slab <= chunk size), but not below 4 KiB; the number of
+    // workgroups grows accordingly so the bytes in flight stay the same.
+    int tl = pa.tile_log2;
+    uint64_t grid64 = wgs_at_plan_tile;
+    while (tl > 12 && (1ull << tl) > pa.ss) {
+        --tl;
+        grid64 *= 2;
+    }
+    if ((1ull << tl) > pa.ss) {
+        // chunks shorter than 4 KiB: one workgroup, or one wavefront, per chunk
+        if (pa.ss > 1024) {
+            hipLaunchKernelGGL(ring_chain_small<kThreads>, dim3((uint32_t)pa.P), dim3(kThreads), 0,
+                               stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.root);
+        } else {
+            const uint32_t per_wg = kThreads / 64;
+            hipLaunchKernelGGL(ring_chain_small<64>, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
+                               dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P,
+                               pa.root);
+        }
         return hipGetLastError();
     }
-    if (grid > n_slabs) grid = n_slabs;
+    const uint64_t n_slabs64 = (pa.n + (1ull << tl) - 1) >> tl;
+    if (n_slabs64 > 0xffffffffull) return hipErrorInvalidValue;
+    const uint32_t n_slabs = (uint32_t)n_slabs64;
+    uint32_t grid = grid64 > n_slabs ? n_slabs : (uint32_t)grid64;
     grid = (grid + 7u) & ~7u;  // whole rounds over the 8 XCDs
     const dim3 g(grid), b(kThreads);
 #define VB_LAUNCH(TL)                                                                       \
     hipLaunchKernelGGL(ring_chain<TL>, g, b, 0, stream, pa.chain, pa.chunk_off, pa.bases,   \
                        pa.P, pa.root, pa.n, pa.ss, n_slabs)
-    switch (pa.tile_log2) {
+    switch (tl) {
         case 12: VB_LAUNCH(12); break;
         case 13: VB_LAUNCH(13); break;
         case 14: VB_LAUNCH(14); break;

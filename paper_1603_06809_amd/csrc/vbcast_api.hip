@@ -92,9 +92,7 @@ int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
     if (plan->ring_executor == VBCAST_RING_CHAINS) {
-        const uint64_t tile = 1ull << pa.tile_log2;
-        const uint32_t n_slabs = (uint32_t)((pa.n + tile - 1) >> pa.tile_log2);
-        hipError_t e = vbcast::launch_ring_chain(pa, n_slabs, plan->chain_grid, stream);
+        hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, stream);
         if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
         return VBCAST_SUCCESS;
     }

@@ -80,8 +80,9 @@ hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *
                             uint32_t n_tiles, int tile_log2, hipStream_t stream);
 
 // Enqueue the ring phase as one launch that walks every slab of the message
-// through all ring steps; `grid` persistent workgroups share `n_slabs` slabs.
-hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t n_slabs, uint32_t grid,
-                             hipStream_t stream);
+// through all ring steps.  `wgs_at_plan_tile` persistent workgroups would share
+// the slabs at the plan's tile size; the launch may pick a smaller slab (and
+// proportionally more workgroups) or one wavefront per chunk for short chunks.
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream);
 
 }  // namespace vbcast

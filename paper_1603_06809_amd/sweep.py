@@ -1,0 +1,93 @@
+"""Sweep over the (process count, message size) points of the paper's three
+experiments [Sec. V]: long messages on 16, 64 and 256 processes; 12288,
+524287 and 1048576 bytes on 9, 17, 33, 65 and 129 processes; 12288 to 2560000
+bytes on 129 processes.  For every point the native and the tuned broadcast
+are timed as graph launches on one GPU and set side by side.
+
+    python -m paper_1603_06809_amd.sweep [--iters 100] [--markdown]
+
+Columns: bytes moved by each schedule and their ratio, time per broadcast,
+tuned/native time ratio, and the paper's "bandwidth" figure - message bytes
+per second of one broadcast, in MB/s with MB = 2**20 [Sec. V].  The paper's
+protocol is a barrier followed by 100 iterations; here that is a stream
+synchronisation followed by ``--iters`` graph launches.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+
+def points():
+    long_sizes = [524_288, 1_048_576, 2_097_152, 4_194_304, 8_388_608, 16_777_216, 30_000_000]
+    pts = [("lmsg-pof2", P, n) for P in (16, 64, 256) for n in long_sizes]
+    pts += [("npof2", P, n) for n in (12_288, 524_287, 1_048_576) for P in (9, 17, 33, 65, 129)]
+    pts += [("P129", 129, n) for n in (12_288, 49_152, 196_608, 524_288, 1_048_576, 2_560_000)]
+    return pts
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--iters", type=int, default=100)
+    ap.add_argument("--markdown", action="store_true")
+    ap.add_argument("--ring-executor", choices=["chains", "steps"], default="chains")
+    args = ap.parse_args()
+
+    import torch
+    from . import vbcast as V
+
+    if not torch.cuda.is_available():
+        print("sweep: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    V.lib()
+    V.vbcast_set_ring_executor(V.RING_CHAINS if args.ring_executor == "chains" else V.RING_STEPS)
+
+    rows = []
+    for (exp, P, n) in points():
+        stride = (n + 255) // 256 * 256
+        bufs = [torch.empty(stride, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        torch.manual_seed(P * 1_000_003 + n)
+        bufs[0].random_()
+        comm = V.Comm([b.data_ptr() for b in bufs], stride)
+        rec = {"experiment": exp, "P": P, "n": n}
+        for algo in ("native", "tuned"):
+            plan = V.bcast_plan(comm, n, 1, 0, algo)
+            for _ in range(3):
+                V.bcast_run(plan)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.iters):
+                V.bcast_run(plan)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) / args.iters * 1e6
+            info = plan.info()
+            rec[algo] = {"us": round(us, 2), "bytes_moved": int(info.bytes_moved),
+                         "MBps": round(n / (us * 1e-6) / 2**20, 1),
+                         "hbm_gbs": round(2.0 * info.bytes_moved / (us * 1e-6) / 1e9, 1)}
+            plan.destroy()
+        ok = all(bool(torch.equal(b[:n], bufs[0][:n])) for b in bufs)
+        rec["ok"] = ok
+        rec["bytes_ratio"] = round(rec["tuned"]["bytes_moved"] / rec["native"]["bytes_moved"], 4)
+        rec["time_ratio"] = round(rec["tuned"]["us"] / rec["native"]["us"], 4)
+        rows.append(rec)
+        comm.destroy()
+        del bufs
+        if not args.markdown:
+            print(json.dumps(rec), flush=True)
+    if args.markdown:
+        print("| experiment | P | n | bytes tuned/native | native us | tuned us | time tuned/native | "
+              "native MB/s | tuned MB/s | tuned HBM GB/s | ok |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|")
+        for r in rows:
+            print(f"| {r['experiment']} | {r['P']} | {r['n']} | {r['bytes_ratio']} | {r['native']['us']} | "
+                  f"{r['tuned']['us']} | {r['time_ratio']} | {r['native']['MBps']} | {r['tuned']['MBps']} | "
+                  f"{r['tuned']['hbm_gbs']} | {r['ok']} |")
+    return 0 if all(r["ok"] for r in rows) else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())
