@@ -27,6 +27,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs (profiles/), scaled by what the same counters read for a plain
+# copy of known size.  Valid only for the configuration it was measured on.
+MEASURED_TRAFFIC = {
+    ("P513_n128M", "chains", 8192, 2): 69.80e9,   # ring_chain: 1.56 GB read + 68.24 GB written
+    ("P513_n128M", "steps", 8192, 2): 268.2e6,    # step_copy, one ring step: 134.2 MB + 134.0 MB
+}
+
 
 def cpu_baseline(w, shrink: int):
     """The oracle as it stands on a bounded sample: same P and root, message
@@ -173,10 +181,15 @@ def main() -> int:
             alg_bytes = 2.0 * float(ring_bytes.sum()) / launches
             kernel = "step_copy (one launch per ring step, tuned)"
         achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
+        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, int(info.tile_bytes),
+                                        args.chain_wgs_per_cu or 2))
+        if args.pad:
+            traffic = None
         roof = {
             "bound": "hbm", "kernel": kernel,
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "traffic_gbs": None if traffic is None else round(traffic / (avg_ms * 1e-3) / 1e9, 1),
             "launches_per_bcast": launches, "avg_launch_us": round(avg_ms * 1e3, 2),
             "algorithmic_bytes_per_launch": int(alg_bytes),
         }
