@@ -23,10 +23,17 @@ rank decides from its own variables what it sends and what it expects, and the
 oracle then checks that every posted send meets a posted receive with the same
 extent before delivering it.  Nothing is blocked, fused or reordered.
 
+* the two neighbouring algorithms of the same MPI_Bcast that the paper names
+  without describing them - binomial-tree broadcast and scatter + recursive-
+  doubling allgather, in their textbook form - and the size / process-count
+  rule that selects among the three                    [Abstract, Sec. I, Sec. V]
+
 Parity pins: every function here is pinned by tests/test_oracle_*.py against
 the paper's worked examples (P = 8 and P = 10), closed forms, the definition of
-broadcast, an independent ownership-set model and an asynchronous mailbox
-execution.  No function is "parity unpinned".
+broadcast, independent ownership-set models and an asynchronous mailbox
+execution.  No function is "parity unpinned"; for the two neighbouring
+algorithms the paper prints no numbers, so their pins are the mathematics only
+(closed forms, invariants, brute force, the definition of broadcast).
 """
 
 from __future__ import annotations
@@ -36,8 +43,13 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
-NATIVE = "native"
-TUNED = "tuned"
+NATIVE = "native"            # scatter + native ring allgather
+TUNED = "tuned"              # scatter + tuned ring allgather
+BINOMIAL = "binomial"        # binomial-tree broadcast of the whole message
+SCATTER_RDB = "scatter_rdb"  # scatter + recursive-doubling allgather (power-of-two P)
+
+SHORT_MSG_BYTES = 12288      # below: short message            [Sec. V]
+LONG_MSG_BYTES = 524288      # from here on: long message      [Sec. V]
 
 RECV_ONLY = 1  # the listing's flag = 1
 SEND_ONLY = 0  # the listing's flag = 0
@@ -241,6 +253,89 @@ def ring_steps(P: int, root: int, n: int, algo: str) -> RingResult:
 
 
 # --------------------------------------------------------------------------
+# the neighbouring algorithms of the same MPI_Bcast          [Abstract, Sec. I]
+#
+# The paper names them (binomial dissemination for short messages,
+# recursive-doubling exchange for medium messages on a power-of-two process
+# count) and gives the size thresholds that select between them [Sec. V], but
+# does not describe them; they are written here in their textbook form, the
+# one of the MPICH collectives paper this paper cites.
+# --------------------------------------------------------------------------
+
+def binomial_levels(P: int, root: int, n: int):
+    """Binomial-tree broadcast: the same tree as the scatter, but every edge
+    carries the whole message.  Level by level from the largest distance, a
+    rank that already has the message hands it to the rank ``mask`` above.
+    Returns (levels, posted): rows with len > 0 per level, and the number of
+    sends posted per level (zero-length ones included)."""
+    levels: List[List[Row]] = []
+    posted: List[int] = []
+    mask = ceil_pow2(P) // 2
+    while mask >= 1:
+        rows: List[Row] = []
+        count = 0
+        for rho in range(0, P, 2 * mask):
+            child = rho + mask
+            if child < P:
+                count += 1
+                if n > 0:
+                    rows.append((absolute_rank(rho, root, P), absolute_rank(child, root, P), 0, n))
+        levels.append(rows)
+        posted.append(count)
+        mask //= 2
+    return levels, posted
+
+
+def recursive_doubling_steps(P: int, root: int, n: int):
+    """Recursive-doubling allgather after the scatter, for a power-of-two P.
+
+    Every rank acts as if it held only its own chunk.  In exchange k (distance
+    2**k) the rank with relative rank rho swaps with rho XOR 2**k everything it
+    has gathered so far: the 2**k chunks of the aligned block that contains
+    rho.  After log2 P exchanges every rank has all P chunks.
+    Returns (steps, posted): rows with len > 0 per exchange, and the number of
+    sends posted per exchange (zero-length ones included).
+    """
+    if P & (P - 1):
+        raise ValueError("recursive doubling needs a power-of-two process count")
+    steps, posted = [], []
+    dist = 1
+    while dist < P:
+        sends, recvs = {}, {}
+        for rho in range(P):
+            partner = rho ^ dist
+            mine = (rho // dist) * dist          # block gathered so far
+            theirs = (partner // dist) * dist
+            s_disp = chunk_extent(mine, n, P)[0]
+            s_count = sum(chunk_extent(c, n, P)[1] for c in range(mine, mine + dist))
+            r_disp = chunk_extent(theirs, n, P)[0]
+            r_count = sum(chunk_extent(c, n, P)[1] for c in range(theirs, theirs + dist))
+            a, b = absolute_rank(rho, root, P), absolute_rank(partner, root, P)
+            sends[(a, b)] = (s_disp, s_count)
+            recvs[(b, a)] = (r_disp, r_count)
+        if sends != recvs:
+            raise AssertionError("recursive doubling: sends and receives do not pair up")
+        posted.append(len(sends))
+        steps.append([(src, dst, d, cnt) for (src, dst), (d, cnt) in sends.items() if cnt > 0])
+        dist *= 2
+    return steps, posted
+
+
+def select_algorithm(n: int, P: int, tuned: bool) -> str:
+    """Which algorithm MPICH's broadcast takes for n bytes on P processes, as
+    the paper states it [Abstract; Sec. I; thresholds in Sec. V]: short messages
+    go down a binomial tree; medium messages on a power-of-two process count
+    use scatter + recursive doubling; long messages, and medium messages on any
+    other process count, use scatter + ring allgather - the native ring, or the
+    paper's tuned one."""
+    if n < SHORT_MSG_BYTES:
+        return BINOMIAL
+    if n < LONG_MSG_BYTES and P & (P - 1) == 0:
+        return SCATTER_RDB
+    return TUNED if tuned else NATIVE
+
+
+# --------------------------------------------------------------------------
 # the whole schedule
 # --------------------------------------------------------------------------
 
@@ -253,7 +348,7 @@ class Schedule:
     ss: int
     n_scatter_steps: int
     steps: List[List[Row]] = field(default_factory=list)  # scatter levels, then ring steps
-    ring_msgs_issued: int = 0   # ring sends posted, zero-length ones included
+    ring_msgs_issued: int = 0   # sends posted after the scatter, zero-length ones included
 
     @property
     def n_steps(self) -> int:
@@ -283,13 +378,22 @@ class Schedule:
 
 
 def build_schedule(P: int, root: int, n: int, algo: str) -> Schedule:
-    """Scatter levels followed by ring steps; one level or ring step = one step.
-
-    Rows inside a step are ordered by the sender's relative rank.
+    """Scatter levels followed by ring steps (or recursive-doubling exchanges),
+    or the levels of the binomial broadcast; one level / ring step / exchange =
+    one step.  Rows inside a step are ordered by the sender's relative rank.
     """
     if P < 1 or not (0 <= root < P) or n < 0:
         raise ValueError("bad (P, root, n)")
+    if algo == BINOMIAL:
+        tree, posted = binomial_levels(P, root, n)
+        return Schedule(P=P, root=root, n=n, algo=algo, ss=scatter_size(n, P),
+                        n_scatter_steps=0, steps=tree, ring_msgs_issued=sum(posted))
     levels = scatter_levels(P, root, n)
+    if algo == SCATTER_RDB:
+        steps, posted = recursive_doubling_steps(P, root, n)
+        return Schedule(P=P, root=root, n=n, algo=algo, ss=scatter_size(n, P),
+                        n_scatter_steps=len(levels), steps=levels + steps,
+                        ring_msgs_issued=sum(posted))
     ring = ring_steps(P, root, n, algo)
     return Schedule(P=P, root=root, n=n, algo=algo, ss=scatter_size(n, P),
                     n_scatter_steps=len(levels),

@@ -10,6 +10,7 @@ import pytest
 
 import test_oracle_pins as pins
 import test_oracle_mailbox as mailbox
+import test_oracle_mpich_paths as paths
 
 SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "oracle", "bcast_oracle.py")
@@ -56,6 +57,25 @@ MUTANTS = {
     "delivery reads the receiver's buffer": (
         "payloads = [bufs[src][off:off + length].copy() for (src, _dst, off, length) in rows]",
         "payloads = [bufs[_dst][off:off + length].copy() for (src, _dst, off, length) in rows]"),
+    "binomial: children sent a chunk instead of the message": (
+        "rows.append((absolute_rank(rho, root, P), absolute_rank(child, root, P), 0, n))",
+        "rows.append((absolute_rank(rho, root, P), absolute_rank(child, root, P), 0, scatter_size(n, P)))"),
+    "binomial: levels smallest distance first": (
+        "    posted: List[int] = []\n    mask = ceil_pow2(P) // 2\n    while mask >= 1:",
+        "    posted: List[int] = []\n    for mask in [1 << k for k in range(ceil_log2(P))]:"),
+    "doubling: partner one rank away instead of one bit away": (
+        "partner = rho ^ dist", "partner = (rho + dist) % P"),
+    "doubling: only the own chunk is swapped": (
+        "s_count = sum(chunk_extent(c, n, P)[1] for c in range(mine, mine + dist))",
+        "s_count = chunk_extent(rho, n, P)[1]"),
+    "doubling: block start not aligned": (
+        "mine = (rho // dist) * dist          # block gathered so far", "mine = rho"),
+    "selection: long threshold off by one": (
+        "if n < LONG_MSG_BYTES and P & (P - 1) == 0:", "if n <= LONG_MSG_BYTES and P & (P - 1) == 0:"),
+    "selection: short threshold off by one": (
+        "if n < SHORT_MSG_BYTES:", "if n <= SHORT_MSG_BYTES:"),
+    "selection: power-of-two test inverted": (
+        "if n < LONG_MSG_BYTES and P & (P - 1) == 0:", "if n < LONG_MSG_BYTES and P & (P - 1) != 0:"),
     "zero-length rows kept": (
         "for (src, dst), (disp, cnt) in sends.items() if cnt > 0]",
         "for (src, dst), (disp, cnt) in sends.items()]"),
@@ -97,6 +117,14 @@ def run_pin_suite():
     pins.test_degenerate_cases()
     mailbox.test_async_execution_agrees_with_the_tables(10, 5, 32)
     mailbox.test_async_execution_agrees_with_the_tables(9, 8, 10)
+    for P in (5, 8, 13):
+        paths.test_binomial_broadcast_tree_and_counts(P)
+    paths.test_binomial_tree_is_the_scatter_tree_of_the_paper()
+    for k in (0, 2, 3):
+        paths.test_recursive_doubling_matches_the_set_model(k)
+    paths.test_final_state_and_independent_rows(8, 7, 1000)
+    paths.test_async_execution(8, 7, 200)
+    paths.test_selection_thresholds()
 
 
 def test_unmutated_oracle_passes_the_compact_suite():
@@ -109,6 +137,7 @@ def test_pins_reject_mutant(name, monkeypatch):
     mutant = load_mutant(old, new)
     monkeypatch.setattr(pins, "O", mutant)
     monkeypatch.setattr(mailbox, "O", mutant)
+    monkeypatch.setattr(paths, "O", mutant)
     with pytest.raises(BaseException) as info:
         run_pin_suite()
     assert not isinstance(info.value, (KeyboardInterrupt, SystemExit))
