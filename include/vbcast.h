@@ -13,15 +13,24 @@
  * rank's buffer equal the root's [Sec. III-A]; bytes at offsets >= n are never
  * touched.
  *
- * Two schedules are provided [Sec. III-A and Sec. IV]:
+ * Two schedules are the subject of the paper [Sec. III-A and Sec. IV]:
  *   VBCAST_NATIVE  scatter + "enclosed" ring: every rank sends and receives one
  *                  chunk in each of the P-1 ring steps;
  *   VBCAST_TUNED   scatter + "non-enclosed" ring: a rank stops receiving once it
  *                  holds the whole message and its left neighbour stops sending
  *                  to it; same number of steps, fewer bytes.
+ * Two more are the neighbouring algorithms of the same MPI_Bcast, which the paper
+ * names [Abstract, Sec. I] and which complete the selection by message size and
+ * process count (vbcast_select_algo):
+ *   VBCAST_BINOMIAL     the whole message goes down the binomial tree, one level
+ *                       per step (short messages);
+ *   VBCAST_SCATTER_RDB  scatter, then log2 P exchanges in which a rank swaps all
+ *                       it has gathered with the rank whose relative rank differs
+ *                       in one bit (medium messages, power-of-two P only).
  *
  * A schedule is a list of steps: ceil(log2 P) scatter levels, then P-1 ring
- * steps.  A step is a table of rows (src rank, dst rank, byte offset, byte
+ * steps (or log2 P exchanges; the binomial broadcast is ceil(log2 P) tree levels
+ * and has no scatter).  A step is a table of rows (src rank, dst rank, byte offset, byte
  * length), ordered by the sender's rank relative to the root; a row means
  * "copy length bytes at that offset from src's buffer to the same offset in
  * dst's buffer".  Rows with length 0 are not stored.  All rows of a step are
@@ -55,7 +64,16 @@ extern "C" {
 typedef struct vbcast_comm vbcast_comm; /* P virtual ranks = P device buffers */
 typedef struct vbcast_plan vbcast_plan; /* tables, tile maps, instantiated graph */
 
-enum { VBCAST_NATIVE = 0, VBCAST_TUNED = 1 };
+enum {
+    VBCAST_NATIVE = 0,      /* scatter + native ring allgather            */
+    VBCAST_TUNED = 1,       /* scatter + tuned ring allgather             */
+    VBCAST_BINOMIAL = 2,    /* binomial-tree broadcast of the whole message */
+    VBCAST_SCATTER_RDB = 3  /* scatter + recursive-doubling allgather, power-of-two P */
+};
+
+/* Message-size classes of MPICH's broadcast [Sec. V]. */
+#define VBCAST_SHORT_MSG_BYTES 12288  /* below: short message        */
+#define VBCAST_LONG_MSG_BYTES 524288  /* from here on: long message  */
 
 /* How bcast_run executes the ring phase (see vbcast_set_ring_executor). */
 enum { VBCAST_RING_STEPS = 0, VBCAST_RING_CHAINS = 1 };
@@ -100,7 +118,8 @@ int vbcast_comm_destroy(vbcast_comm *comm);
  *   comm        communicator; must outlive the plan.
  *   count, dtype_size   message = count * dtype_size bytes; 0 is valid.
  *   root        absolute rank in [0, P).
- *   algo        VBCAST_NATIVE or VBCAST_TUNED.
+ *   algo        VBCAST_NATIVE, VBCAST_TUNED, VBCAST_BINOMIAL or VBCAST_SCATTER_RDB
+ *               (the last one needs a power-of-two P: ARG otherwise).
  *   hip_stream  stream the generation kernels run on; the call synchronises
  *               this stream before it returns (it reads per-step counts back).
  *   out         host pointer receiving the handle.
@@ -148,15 +167,17 @@ int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms);
 
 typedef struct vbcast_plan_info {
     int32_t P, root, algo;
-    int32_t n_scatter_steps; /* ceil(log2 P) */
-    int32_t n_steps;         /* n_scatter_steps + P - 1; 0 for P = 1 */
+    int32_t n_scatter_steps; /* ceil(log2 P); 0 for VBCAST_BINOMIAL */
+    int32_t n_steps;         /* scatter steps + P - 1 ring steps (or log2 P exchanges, or
+                                ceil(log2 P) tree levels); 0 for P = 1 */
     int32_t tile_bytes;      /* copy tile size the plan was built for */
     uint64_t n;              /* message bytes */
     uint64_t ss;             /* chunk size ceil(n / P) */
-    uint64_t scatter_rows, ring_rows;   /* stored rows (length > 0) */
+    uint64_t scatter_rows, ring_rows;   /* stored rows (length > 0); "ring" = every step
+                                           after the scatter, whatever the algorithm */
     uint64_t scatter_bytes, ring_bytes; /* bytes moved, one direction */
     uint64_t bytes_moved;               /* scatter_bytes + ring_bytes */
-    uint64_t ring_msgs_issued; /* ring sends the ranks post, zero-length ones included
+    uint64_t ring_msgs_issued; /* sends the ranks post after the scatter, zero-length ones included
                                   [Sec. III-A: P (P - 1) native; Sec. IV: fewer tuned] */
     uint64_t pairing_mismatches; /* ring (step, rank) pairs where the sender's and the
                                     receiver's own decisions disagree; always 0 */
@@ -202,6 +223,17 @@ int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles
                             uint32_t *tile_row, uint32_t *tile_idx);
 
 int bcast_plan_destroy(vbcast_plan *plan);
+
+/*
+ * The algorithm MPICH's broadcast takes for nbytes on P processes, as the paper
+ * states it [Abstract; Sec. I; thresholds in Sec. V]: short messages (below
+ * VBCAST_SHORT_MSG_BYTES) -> VBCAST_BINOMIAL; medium messages on a power-of-two P
+ * -> VBCAST_SCATTER_RDB; long messages (from VBCAST_LONG_MSG_BYTES) and medium
+ * messages on any other P -> scatter + ring allgather: VBCAST_TUNED if `tuned` is
+ * non-zero, else VBCAST_NATIVE.  Host only, no GPU call.  *algo is a host pointer.
+ * Errors: ARG (null, P < 1).
+ */
+int vbcast_select_algo(size_t nbytes, int P, int tuned, int *algo);
 
 /*
  * Copy-tile size used by plans created afterwards: a power of two between 4096

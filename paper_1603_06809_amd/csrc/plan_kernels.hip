@@ -143,6 +143,9 @@ __global__ __launch_bounds__(kThreads) void plan_descriptors(PlanArrays pa) {
 // relative rank rho that is a multiple of 2m and has rho + m < P sends the
 // chunks [rho + m, min(rho + 2m, P)) as one message to rho + m.
 //
+// Binomial-broadcast level and recursive-doubling exchange [Abstract, Sec. I: the
+// neighbouring algorithms, named there]: see the two branches below.
+//
 // Ring step i = 1..P-1 [Sec. III-A Fig. 3; Sec. IV listing]: the rank with
 // relative rank rho sends the chunk with relative index (rho - i + 1) mod P to
 // its right neighbour.  NATIVE posts every such send.  TUNED posts it while
@@ -157,9 +160,16 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
 
     const int P = pa.P;
     const int s = blockIdx.x;
-    const bool scatter = s < pa.L;
-    const int m = scatter ? (1 << (pa.L - 1 - s)) : 0;
-    const int i = s - pa.L + 1;
+    // what kind of step this is
+    enum { SCATTER, RING, TREE, EXCHANGE };
+    int kind;
+    if (s < pa.n_scatter) kind = SCATTER;
+    else if (pa.algo == 2) kind = TREE;
+    else if (pa.algo == 3) kind = EXCHANGE;
+    else kind = RING;
+    const int m = (kind == SCATTER || kind == TREE) ? (1 << (pa.L - 1 - s)) : 0;  // tree distance
+    const int i = s - pa.n_scatter + 1;                                          // ring step
+    const int dist = kind == EXCHANGE ? (1 << (s - pa.n_scatter)) : 0;           // exchange distance
     const int tl = pa.tile_log2;
 
     Row *rows = pa.rows + (size_t)s * P;
@@ -174,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
         int dst_rel = 0;
         uint64_t off = 0, len = 0;
         if (rho < P) {
-            if (scatter) {
+            if (kind == SCATTER) {
                 if ((rho & (2 * m - 1)) == 0 && rho + m < P) {
                     dst_rel = rho + m;
                     const int end = (rho + 2 * m < P) ? rho + 2 * m : P;
@@ -182,6 +192,22 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
                     len = pa.chunk_off[end] - off;
                     posted = len > 0;
                 }
+            } else if (kind == TREE) {
+                // binomial broadcast: the scatter's tree, the whole message on every edge
+                if ((rho & (2 * m - 1)) == 0 && rho + m < P) {
+                    dst_rel = rho + m;
+                    off = 0;
+                    len = pa.n;
+                    posted = true;
+                }
+            } else if (kind == EXCHANGE) {
+                // recursive doubling: swap the aligned block gathered so far with the
+                // rank whose relative rank differs in this one bit
+                const int mine = rho & ~(dist - 1);
+                dst_rel = rho ^ dist;
+                off = pa.chunk_off[mine];
+                len = pa.chunk_off[mine + dist] - off;
+                posted = true;
             } else {
                 int c = rho + 1 - i;
                 if (c < 0) c += P;
@@ -203,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
             }
         }
         const bool valid = posted && len > 0;
-        if (!scatter && rho < P) {
+        if (kind == RING && rho < P) {
             // the same decision, filed under the chunk instead of the step
             int c = rho + 1 - i;
             if (c < 0) c += P;

@@ -87,22 +87,24 @@ int launch_steps(const vbcast_plan *plan, int first, int last, hipStream_t strea
     return VBCAST_SUCCESS;
 }
 
-// The ring phase the way the plan's graph runs it.
+// The steps after the scatter, the way the plan's graph runs them.
 int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
-    if (plan->ring_executor == VBCAST_RING_CHAINS) {
+    const bool ring_algo = pa.algo == VBCAST_NATIVE || pa.algo == VBCAST_TUNED;
+    if (ring_algo && plan->ring_executor == VBCAST_RING_CHAINS) {
         hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, stream);
         if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
         return VBCAST_SUCCESS;
     }
-    return launch_steps(plan, pa.L, pa.n_steps, stream, nullptr);
+    return launch_steps(plan, pa.n_scatter, pa.n_steps, stream, nullptr);
 }
 
 int graph_tile_map_steps(const vbcast_plan *plan) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return 0;
-    return plan->ring_executor == VBCAST_RING_CHAINS ? pa.L : pa.n_steps;
+    const bool ring_algo = pa.algo == VBCAST_NATIVE || pa.algo == VBCAST_TUNED;
+    return ring_algo && plan->ring_executor == VBCAST_RING_CHAINS ? pa.n_scatter : pa.n_steps;
 }
 
 int build_graph(vbcast_plan *plan) {
@@ -119,7 +121,7 @@ int build_graph(vbcast_plan *plan) {
     // only the scatter levels need theirs rebuilt.
     e = vbcast::launch_plan_kernels(pa, graph_tile_map_steps(plan), cap);
     if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
-    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, pa.n_steps ? pa.L : 0, cap, nullptr);
+    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, pa.n_steps ? pa.n_scatter : 0, cap, nullptr);
     if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, cap);
     hipGraph_t graph = nullptr;
     e = hipStreamEndCapture(cap, &graph);
@@ -206,14 +208,21 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     if (!out) return VBCAST_ERR_ARG;
     *out = nullptr;
     if (!comm) return VBCAST_ERR_ARG;
-    if (algo != VBCAST_NATIVE && algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
+    if (algo < VBCAST_NATIVE || algo > VBCAST_SCATTER_RDB) return VBCAST_ERR_ARG;
     const int P = comm->P;
+    if (algo == VBCAST_SCATTER_RDB && (P & (P - 1)) != 0) return VBCAST_ERR_ARG;
     if (root < 0 || root >= P) return VBCAST_ERR_ROOT;
     if (dtype_size != 0 && count > SIZE_MAX / dtype_size) return VBCAST_ERR_COUNT;
     const uint64_t n = (uint64_t)count * (uint64_t)dtype_size;
     if (n > comm->buf_bytes) return VBCAST_ERR_COUNT;
     const int tile_log2 = g_tile_log2.load();
-    const uint64_t tile_cap64 = (n >> tile_log2) + 2ull * (uint64_t)P + 1ull;
+    // Most bytes any one step moves: n for scatter levels and ring steps; the last
+    // tree level of the binomial broadcast and the last recursive-doubling
+    // exchange move P/2 messages' worth.
+    const bool ring_algo = algo == VBCAST_NATIVE || algo == VBCAST_TUNED;
+    const uint64_t per_step = ring_algo ? 1ull : (uint64_t)(P / 2 > 0 ? P / 2 : 1);
+    if (n != 0 && per_step > (~0ull >> 1) / n) return VBCAST_ERR_COUNT;
+    const uint64_t tile_cap64 = ((n * per_step) >> tile_log2) + 2ull * (uint64_t)P + 1ull;
     if (tile_cap64 >= (1ull << 31)) return VBCAST_ERR_COUNT;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -225,7 +234,11 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     pa.root = root;
     pa.algo = algo;
     pa.L = ceil_log2_int(P);
-    pa.n_steps = P > 1 ? pa.L + P - 1 : 0;
+    pa.n_scatter = algo == VBCAST_BINOMIAL ? 0 : pa.L;
+    pa.n_steps = P <= 1 ? 0
+                 : algo == VBCAST_BINOMIAL ? pa.L
+                 : algo == VBCAST_SCATTER_RDB ? 2 * pa.L
+                                              : pa.L + P - 1;
     pa.tile_log2 = tile_log2;
     pa.tile_cap = (uint32_t)tile_cap64;
     pa.n = n;
@@ -241,7 +254,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     const size_t o_sw_step = lay.take(sizeof(int32_t) * Pz);
     const size_t o_sw_flag = lay.take(sizeof(int32_t) * Pz);
     const size_t o_rows = lay.take(sizeof(Row) * S * Pz);
-    const size_t o_chain = lay.take(sizeof(uint64_t) * Pz * (Pz - 1));
+    const size_t o_chain = lay.take(ring_algo ? sizeof(uint64_t) * Pz * (Pz - 1) : 0);
     const size_t o_tile_ptr = lay.take(sizeof(uint32_t) * S * (Pz + 1));
     const size_t o_tiles = lay.take(sizeof(Tile) * S * (size_t)pa.tile_cap);
     const size_t o_step_rows = lay.take(sizeof(uint32_t) * S);
@@ -397,7 +410,7 @@ int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms) 
     }
     mark(1);
     if (rc == VBCAST_SUCCESS)
-        rc = launch_steps(plan, 0, plan->pa.n_steps ? plan->pa.L : 0, stream, nullptr);
+        rc = launch_steps(plan, 0, plan->pa.n_steps ? plan->pa.n_scatter : 0, stream, nullptr);
     mark(2);
     if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, stream);
     mark(3);
@@ -421,13 +434,13 @@ int bcast_plan_info(const vbcast_plan *plan, vbcast_plan_info *info) {
     info->P = pa.P;
     info->root = pa.root;
     info->algo = pa.algo;
-    info->n_scatter_steps = pa.n_steps ? pa.L : 0;
+    info->n_scatter_steps = pa.n_steps ? pa.n_scatter : 0;
     info->n_steps = pa.n_steps;
     info->tile_bytes = 1 << pa.tile_log2;
     info->n = pa.n;
     info->ss = pa.ss;
     for (int s = 0; s < pa.n_steps; ++s) {
-        const bool scatter = s < pa.L;
+        const bool scatter = s < pa.n_scatter;
         (scatter ? info->scatter_rows : info->ring_rows) += plan->step_rows[s];
         (scatter ? info->scatter_bytes : info->ring_bytes) += plan->step_bytes[s];
         if (!scatter) info->ring_msgs_issued += plan->step_posted[s];
@@ -499,6 +512,17 @@ int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles
             if (tile_idx) tile_idx[k] = tmp[k].idx;
         }
     }
+    return VBCAST_SUCCESS;
+}
+
+int vbcast_select_algo(size_t nbytes, int P, int tuned, int *algo) {
+    if (!algo || P < 1) return VBCAST_ERR_ARG;
+    if (nbytes < VBCAST_SHORT_MSG_BYTES)
+        *algo = VBCAST_BINOMIAL;
+    else if (nbytes < VBCAST_LONG_MSG_BYTES && (P & (P - 1)) == 0)
+        *algo = VBCAST_SCATTER_RDB;
+    else
+        *algo = tuned ? VBCAST_TUNED : VBCAST_NATIVE;
     return VBCAST_SUCCESS;
 }
 

@@ -28,8 +28,9 @@ struct Tile {
 // per step (`P` rows, `P + 1` tile-scan entries, `tile_cap` tiles).
 struct PlanArrays {
     int32_t P, root, algo;
-    int32_t L;          // scatter levels = ceil(log2 P)
-    int32_t n_steps;    // L + P - 1 (0 when P == 1)
+    int32_t L;          // ceil(log2 P)
+    int32_t n_scatter;  // scatter steps: L, or 0 for the binomial broadcast
+    int32_t n_steps;    // all steps (0 when P == 1)
     int32_t tile_log2;
     uint32_t tile_cap;  // tile slots per step
     uint64_t n, ss;

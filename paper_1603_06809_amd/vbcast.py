@@ -20,7 +20,10 @@ LIB_PATH = os.path.join(_HERE, "libvbcast.so")
 
 NATIVE = 0
 TUNED = 1
-ALGOS = {"native": NATIVE, "tuned": TUNED}
+BINOMIAL = 2
+SCATTER_RDB = 3
+ALGOS = {"native": NATIVE, "tuned": TUNED, "binomial": BINOMIAL, "scatter_rdb": SCATTER_RDB}
+ALGO_NAMES = {v: k for k, v in ALGOS.items()}
 
 RING_STEPS = 0
 RING_CHAINS = 1
@@ -31,7 +34,8 @@ EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
     "bcast_plan_export_tiles", "bcast_plan_destroy", "vbcast_set_tile_bytes",
-    "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "bcast_strerror",
+    "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
+    "bcast_strerror",
 ]
 
 
@@ -86,6 +90,7 @@ def lib():
     L.vbcast_set_tile_bytes.argtypes = [C.c_size_t]
     L.vbcast_set_ring_executor.argtypes = [C.c_int]
     L.vbcast_set_chain_workgroups_per_cu.argtypes = [C.c_int]
+    L.vbcast_select_algo.argtypes = [C.c_size_t, C.c_int, C.c_int, C.POINTER(C.c_int)]
     L.bcast_strerror.argtypes = [C.c_int]
     L.bcast_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -127,6 +132,12 @@ def vbcast_set_ring_executor(mode: int) -> None:
 
 def vbcast_set_chain_workgroups_per_cu(k: int) -> None:
     _check(lib().vbcast_set_chain_workgroups_per_cu(k))
+
+
+def vbcast_select_algo(nbytes: int, P: int, tuned: bool) -> int:
+    out = C.c_int()
+    _check(lib().vbcast_select_algo(nbytes, P, 1 if tuned else 0, C.byref(out)))
+    return out.value
 
 
 class Comm:

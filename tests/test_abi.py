@@ -77,6 +77,19 @@ def test_invalid_arguments_are_rejected_without_a_device():
     assert lib.bcast_run_timed(None, None, None) == V.ERR_ARG
 
 
+def test_select_algo_matches_the_oracle_rule():
+    """Host-only entry point: the size / process-count rule [Sec. V thresholds]."""
+    from oracle import bcast_oracle as O
+    names = {V.NATIVE: O.NATIVE, V.TUNED: O.TUNED, V.BINOMIAL: O.BINOMIAL, V.SCATTER_RDB: O.SCATTER_RDB}
+    for P in (1, 2, 3, 8, 9, 16, 24, 64, 129, 256, 513):
+        for n in (0, 1, 12287, 12288, 12289, 100_000, 524287, 524288, 524289, 30_000_000):
+            for tuned in (False, True):
+                assert names[V.vbcast_select_algo(n, P, tuned)] == O.select_algorithm(n, P, tuned)
+    out = C.c_int()
+    assert V.lib().vbcast_select_algo(10, 0, 0, C.byref(out)) == V.ERR_ARG
+    assert V.lib().vbcast_select_algo(10, 4, 0, None) == V.ERR_ARG
+
+
 def test_error_texts():
     for code in range(7):
         assert V.bcast_strerror(code)

@@ -261,7 +261,7 @@ def test_errors_on_device(V):
     comm = V.Comm.from_tensors(bufs)
     for args, code in [((16, 1, 4, V.NATIVE), V.ERR_ROOT), ((16, 1, -1, V.NATIVE), V.ERR_ROOT),
                        ((257, 1, 0, V.NATIVE), V.ERR_COUNT), ((1 << 62, 8, 0, V.TUNED), V.ERR_COUNT),
-                       ((16, 1, 0, 2), V.ERR_ARG)]:
+                       ((16, 1, 0, 4), V.ERR_ARG), ((16, 1, 0, -1), V.ERR_ARG)]:
         with pytest.raises(V.VbcastError) as e:
             V.bcast_plan(comm, *args)
         assert e.value.code == code
@@ -272,6 +272,70 @@ def test_errors_on_device(V):
         assert e.value.code == V.ERR_ARG
     plan.destroy()
     comm.destroy()
+
+
+# ------------------------------------------------------------------ the neighbouring algorithms
+
+OTHER_SHAPES = [(P, root, n)
+                for P in (1, 2, 3, 4, 7, 8, 13, 16, 32, 33, 64)
+                for root in sorted({0, P - 1})
+                for n in sorted({0, 1, 17, P + 1, 1000, 12_287, 70_001})]
+
+
+@pytest.mark.parametrize("algo", [O.BINOMIAL, O.SCATTER_RDB])
+def test_neighbouring_algorithms_every_step(V, algo):
+    """Binomial-tree broadcast and scatter + recursive doubling: tables exact,
+    state exact after every step, graph run exact."""
+    for (P, root, n) in OTHER_SHAPES:
+        if algo == O.SCATTER_RDB and P & (P - 1):
+            continue
+        w = I.Workload(f"other_{P}_{root}_{n}", P, root, n, seed=5000 + P * 17 + n)
+        state, comm, plan = make(V, w, algo, pad=40)
+        sched = O.build_schedule(P, root, n, algo)
+        check_tables(plan, sched)
+        ref = H.host_buffers(w, pad=40)
+        for s in range(sched.n_steps):
+            plan.run_steps(s, s + 1)
+            O.apply_step(ref, sched.steps[s])
+            assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (P, root, n, algo, s)
+        H.refill(state, w)
+        plan.run()
+        sync()
+        want = np.stack(O.broadcast_definition(H.host_buffers(w, pad=40), root, n))
+        assert np.array_equal(state.cpu().numpy(), want), (P, root, n, algo)
+        plan.destroy()
+        comm.destroy()
+
+
+def test_recursive_doubling_rejects_other_process_counts(V):
+    import torch
+    bufs = [torch.zeros(256, dtype=torch.uint8, device="cuda") for _ in range(6)]
+    comm = V.Comm.from_tensors(bufs)
+    with pytest.raises(V.VbcastError) as e:
+        V.bcast_plan(comm, 64, 1, 0, V.SCATTER_RDB)
+    assert e.value.code == V.ERR_ARG
+    comm.destroy()
+
+
+@pytest.mark.parametrize("P,n", [(16, 4096), (16, 12_288), (16, 524_287), (64, 100_000), (256, 12_288),
+                                 (129, 4096), (9, 12_287), (513, 8192), (64, 524_288)])
+def test_selected_algorithm_runs(V, P, n):
+    """MPI_Bcast as a whole: pick the algorithm by the size / process-count rule
+    (the library's choice must be the oracle's), run it, compare."""
+    for tuned in (False, True):
+        code = V.vbcast_select_algo(n, P, tuned)
+        algo = V.ALGO_NAMES[code]
+        assert algo == O.select_algorithm(n, P, tuned)
+        w = I.Workload(f"auto_{P}_{n}", P, P // 2, n, seed=9000 + P)
+        state, comm, plan = make(V, w, algo)
+        sched = O.build_schedule(P, w.root, n, algo)
+        check_tables(plan, sched)
+        plan.run()
+        sync()
+        want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, n))
+        assert np.array_equal(state.cpu().numpy(), want), (P, n, algo)
+        plan.destroy()
+        comm.destroy()
 
 
 # ------------------------------------------------------------------ the paper's own shapes
