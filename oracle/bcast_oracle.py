@@ -402,6 +402,29 @@ def build_schedule(P: int, root: int, n: int, algo: str) -> Schedule:
 
 
 # --------------------------------------------------------------------------
+# inter-node / intra-node census                                  [Sec. V-A]
+# --------------------------------------------------------------------------
+
+def node_census(sched: Schedule, ranks_per_node: int) -> dict:
+    """Messages and bytes that cross a node boundary when the ranks sit on
+    nodes in blocks of ``ranks_per_node`` (rank r on node r // ranks_per_node;
+    the paper's cluster holds 24 processes per node and places them this way).
+    Counted separately for the scatter and for the steps after it; only rows
+    with len > 0 count."""
+    out = {"scatter_inter_msgs": 0, "scatter_inter_bytes": 0,
+           "scatter_intra_msgs": 0, "scatter_intra_bytes": 0,
+           "ring_inter_msgs": 0, "ring_inter_bytes": 0,
+           "ring_intra_msgs": 0, "ring_intra_bytes": 0}
+    for s, rows in enumerate(sched.steps):
+        phase = "scatter" if s < sched.n_scatter_steps else "ring"
+        for (src, dst, _off, length) in rows:
+            kind = "inter" if src // ranks_per_node != dst // ranks_per_node else "intra"
+            out[f"{phase}_{kind}_msgs"] += 1
+            out[f"{phase}_{kind}_bytes"] += length
+    return out
+
+
+# --------------------------------------------------------------------------
 # executing a schedule on byte buffers
 # --------------------------------------------------------------------------
 

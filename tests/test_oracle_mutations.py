@@ -76,6 +76,12 @@ MUTANTS = {
         "if n < SHORT_MSG_BYTES:", "if n <= SHORT_MSG_BYTES:"),
     "selection: power-of-two test inverted": (
         "if n < LONG_MSG_BYTES and P & (P - 1) == 0:", "if n < LONG_MSG_BYTES and P & (P - 1) != 0:"),
+    "census: nodes counted by relative rank": (
+        'kind = "inter" if src // ranks_per_node != dst // ranks_per_node else "intra"',
+        'kind = "inter" if ((src - sched.root) % sched.P) // ranks_per_node != ((dst - sched.root) % sched.P) // ranks_per_node else "intra"'),
+    "census: ranks dealt round-robin to nodes": (
+        'kind = "inter" if src // ranks_per_node != dst // ranks_per_node else "intra"',
+        'kind = "inter" if src % ranks_per_node != dst % ranks_per_node else "intra"'),
     "zero-length rows kept": (
         "for (src, dst), (disp, cnt) in sends.items() if cnt > 0]",
         "for (src, dst), (disp, cnt) in sends.items()]"),
@@ -125,6 +131,9 @@ def run_pin_suite():
     paths.test_final_state_and_independent_rows(8, 7, 1000)
     paths.test_async_execution(8, 7, 200)
     paths.test_selection_thresholds()
+    pins.test_node_census_closed_forms(64, 17, 999_983, 24)
+    pins.test_node_census_closed_forms(10, 3, 1000, 4)
+    pins.test_node_census_paper_sizes()
 
 
 def test_unmutated_oracle_passes_the_compact_suite():

@@ -422,3 +422,60 @@ def test_chunking():
     assert [O.ceil_pow2(p) for p in (1, 2, 3, 8, 9, 10, 513)] == [1, 2, 4, 8, 16, 16, 1024]
     assert [O.relative_rank(r, 3, 5) for r in range(5)] == [2, 3, 4, 0, 1]
     assert [O.absolute_rank(O.relative_rank(r, 3, 5), 3, 5) for r in range(5)] == list(range(5))
+
+
+# ---------------------------------------------------------------- node census
+
+@pytest.mark.parametrize("P,root,n,rpn", [(16, 0, 524_288, 24), (64, 0, 3_000_000, 24), (64, 17, 999_983, 24),
+                                          (256, 5, 524_288, 24), (129, 128, 12_288, 24), (10, 3, 1000, 4),
+                                          (48, 47, 4800, 24), (50, 0, 77, 7)])
+def test_node_census_closed_forms(P, root, n, rpn):
+    """Sec. V-A: ranks are placed on the nodes in blocks (24 per node on the
+    paper's cluster), so 16 processes never leave their node.  Closed forms for
+    the ring: a step uses every ring edge once, an edge (r -> r+1) carries every
+    chunk but the receiver's own, and the tuned ring drops the receiver's last
+    span - 1 receives."""
+    ss = -(-n // P)
+    clen = [max(0, min(ss, n - c * ss)) for c in range(P)]
+    rel = lambda r: (r - root) % P
+    crossing = [r for r in range(P) if r // rpn != ((r + 1) % P) // rpn]
+    nodes = -(-P // rpn)
+    assert len(crossing) == (nodes if nodes > 1 else 0)
+
+    def span(c):
+        return P if c == 0 else min(c & -c, P - c)
+
+    nat = O.node_census(O.build_schedule(P, root, n, O.NATIVE), rpn)
+    tun = O.node_census(O.build_schedule(P, root, n, O.TUNED), rpn)
+    empty = sum(1 for c in range(P) if clen[c] == 0)
+    # native: every crossing edge carries P - 1 chunks, the empty ones excepted
+    want_msgs = sum((P - 1) - (empty - (1 if clen[rel((r + 1) % P)] == 0 else 0)) for r in crossing)
+    want_bytes = sum(n - clen[rel((r + 1) % P)] for r in crossing)
+    assert nat["ring_inter_msgs"] == want_msgs and nat["ring_inter_bytes"] == want_bytes
+    assert nat["ring_inter_bytes"] + nat["ring_intra_bytes"] == (P - 1) * n
+    # tuned: the receiver behind a crossing edge already holds its subtree's chunks
+    t_bytes = 0
+    for r in crossing:
+        c = rel((r + 1) % P)
+        held = sum(clen[(c + k) % P] for k in range(span(c)))
+        t_bytes += n - held
+    assert tun["ring_inter_bytes"] == t_bytes
+    assert tun["ring_inter_msgs"] <= nat["ring_inter_msgs"]
+    assert tun["scatter_inter_bytes"] == nat["scatter_inter_bytes"]
+    total = sum(v for k, v in tun.items() if k.endswith("bytes"))
+    assert total == (P - 1) * n
+    if P <= rpn:
+        assert nat["ring_inter_msgs"] == nat["scatter_inter_msgs"] == 0   # one node only
+
+
+def test_node_census_paper_sizes():
+    """16 processes stay inside one node; with 64 and 256 the tuned ring sends
+    fewer messages between nodes than the native one (Sec. V-A)."""
+    one = O.node_census(O.build_schedule(16, 0, 524_288, O.TUNED), 24)
+    assert one["ring_inter_msgs"] == 0 and one["scatter_inter_msgs"] == 0
+    for P in (64, 256):
+        nat = O.node_census(O.build_schedule(P, 0, 1_048_576, O.NATIVE), 24)
+        tun = O.node_census(O.build_schedule(P, 0, 1_048_576, O.TUNED), 24)
+        nodes = -(-P // 24)
+        assert nat["ring_inter_msgs"] == nodes * (P - 1)
+        assert tun["ring_inter_msgs"] < nat["ring_inter_msgs"]
