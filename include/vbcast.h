@@ -222,6 +222,25 @@ int bcast_plan_export_desc(const vbcast_plan *plan, uint64_t *chunk_off, uint64_
 int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles,
                             uint32_t *tile_row, uint32_t *tile_idx);
 
+typedef struct vbcast_census {
+    uint64_t scatter_inter_msgs, scatter_inter_bytes; /* scatter rows between nodes   */
+    uint64_t scatter_intra_msgs, scatter_intra_bytes; /* scatter rows inside a node   */
+    uint64_t ring_inter_msgs, ring_inter_bytes;       /* later steps, between nodes   */
+    uint64_t ring_intra_msgs, ring_intra_bytes;       /* later steps, inside a node   */
+} vbcast_census;
+
+/*
+ * Count, on the GPU, the stored rows (length > 0) of the plan that would cross a
+ * node boundary, and their bytes, if the P ranks were MPI processes placed on
+ * nodes in blocks of ranks_per_node (rank r on node r / ranks_per_node) - the
+ * placement of the paper's measurements, 24 processes per node [Sec. V, V-A]; the
+ * paper explains its gains at 64 and 256 processes by the smaller number of
+ * inter-node messages.  Runs on hip_stream and waits for it.  *out is a host
+ * pointer.  Errors: ARG (null, ranks_per_node < 1), HIP.
+ */
+int bcast_plan_census(const vbcast_plan *plan, int ranks_per_node, void *hip_stream,
+                      vbcast_census *out);
+
 int bcast_plan_destroy(vbcast_plan *plan);
 
 /*

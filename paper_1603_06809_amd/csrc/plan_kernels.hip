@@ -313,7 +313,39 @@ __global__ __launch_bounds__(kThreads) void plan_tiles(PlanArrays pa) {
     pa.tiles[(size_t)s * pa.tile_cap + b] = t;
 }
 
+// ---------------------------------------------------------------------------
+// Census.  One workgroup per step walks the step's stored rows and counts
+// those whose two ranks sit on different nodes under blocked placement (rank r
+// on node r / ranks_per_node) [Sec. V-A], and their bytes; wave reductions, then
+// an LDS exchange of the four sums.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void plan_census(PlanArrays pa, int ranks_per_node) {
+    __shared__ uint64_t slots[kWaves];
+    const int s = blockIdx.x;
+    const uint32_t n_rows = pa.step_rows[s];
+    const Row *rows = pa.rows + (size_t)s * pa.P;
+    uint64_t v[4] = {0, 0, 0, 0};
+    for (uint32_t k = threadIdx.x; k < n_rows; k += kThreads) {
+        const Row r = rows[k];
+        const bool inter = (int)r.src / ranks_per_node != (int)r.dst / ranks_per_node;
+        v[inter ? 0 : 2] += 1;
+        v[inter ? 1 : 3] += r.len;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint64_t total;
+        (void)block_exclusive_scan<uint64_t>(v[q], slots, total);
+        if (threadIdx.x == 0) pa.census[(size_t)s * 4 + q] = total;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_plan_census(const PlanArrays &pa, int ranks_per_node, hipStream_t stream) {
+    if (pa.n_steps == 0) return hipSuccess;
+    hipLaunchKernelGGL(plan_census, dim3(pa.n_steps), dim3(kThreads), 0, stream, pa, ranks_per_node);
+    return hipGetLastError();
+}
 
 hipError_t launch_plan_kernels(const PlanArrays &pa, int tile_map_steps, hipStream_t stream) {
     hipLaunchKernelGGL(plan_descriptors, dim3(1), dim3(kThreads), 0, stream, pa);

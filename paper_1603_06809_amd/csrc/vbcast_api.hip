@@ -262,6 +262,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     const size_t o_step_posted = lay.take(sizeof(uint32_t) * S);
     const size_t o_step_mismatch = lay.take(sizeof(uint32_t) * S);
     const size_t o_step_bytes = lay.take(sizeof(uint64_t) * S);
+    const size_t o_census = lay.take(sizeof(uint64_t) * 4 * S);
 
     hipError_t e = hipMalloc(&plan->arena, lay.total);
     if (e != hipSuccess) {
@@ -297,6 +298,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     pa.step_posted = reinterpret_cast<uint32_t *>(base + o_step_posted);
     pa.step_mismatch = reinterpret_cast<uint32_t *>(base + o_step_mismatch);
     pa.step_bytes = reinterpret_cast<uint64_t *>(base + o_step_bytes);
+    pa.census = reinterpret_cast<uint64_t *>(base + o_census);
 
     int rc = VBCAST_SUCCESS;
     e = vbcast::launch_plan_kernels(pa, pa.n_steps, stream);
@@ -510,6 +512,36 @@ int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles
         for (uint32_t k = 0; k < nt; ++k) {
             if (tile_row) tile_row[k] = tmp[k].row;
             if (tile_idx) tile_idx[k] = tmp[k].idx;
+        }
+    }
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_census(const vbcast_plan *plan, int ranks_per_node, void *hip_stream,
+                      vbcast_census *out) {
+    if (!plan || !out || ranks_per_node < 1) return VBCAST_ERR_ARG;
+    std::memset(out, 0, sizeof(*out));
+    const PlanArrays &pa = plan->pa;
+    if (pa.n_steps == 0) return VBCAST_SUCCESS;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = vbcast::launch_plan_census(pa, ranks_per_node, stream);
+    if (e != hipSuccess) return hip_fail(e, "census kernel");
+    std::vector<uint64_t> host((size_t)pa.n_steps * 4);
+    HIP_TRY(hipMemcpyAsync(host.data(), pa.census, host.size() * sizeof(uint64_t),
+                           hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    for (int s = 0; s < pa.n_steps; ++s) {
+        const uint64_t *v = &host[(size_t)s * 4];
+        if (s < pa.n_scatter) {
+            out->scatter_inter_msgs += v[0];
+            out->scatter_inter_bytes += v[1];
+            out->scatter_intra_msgs += v[2];
+            out->scatter_intra_bytes += v[3];
+        } else {
+            out->ring_inter_msgs += v[0];
+            out->ring_inter_bytes += v[1];
+            out->ring_intra_msgs += v[2];
+            out->ring_intra_bytes += v[3];
         }
     }
     return VBCAST_SUCCESS;

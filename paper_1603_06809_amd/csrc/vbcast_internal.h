@@ -52,6 +52,7 @@ struct PlanArrays {
     uint32_t *step_posted;  // [n_steps] sends posted, zero-length included
     uint32_t *step_mismatch;  // [n_steps] sender/receiver decisions that disagree
     uint64_t *step_bytes;   // [n_steps]
+    uint64_t *census;       // [n_steps][4] inter msgs, inter bytes, intra msgs, intra bytes
 };
 
 // Rank buffers are ordinary device allocations.  Pointers that come out of a
@@ -75,6 +76,10 @@ __device__ __forceinline__ gmem_u8 *gmem_bytes(uint8_t *p) { return (gmem_u8 *)(
 // Enqueue the three generation kernels (descriptors, rows, tile maps); tile maps
 // are (re)built for the first `tile_map_steps` steps only.
 hipError_t launch_plan_kernels(const PlanArrays &pa, int tile_map_steps, hipStream_t stream);
+
+// Enqueue the census kernel: per step, rows and bytes that cross / stay inside a
+// node when ranks sit on nodes in blocks of `ranks_per_node`; fills pa.census.
+hipError_t launch_plan_census(const PlanArrays &pa, int ranks_per_node, hipStream_t stream);
 
 // Enqueue the copy kernel of one step; `n_tiles` > 0 workgroups.
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,

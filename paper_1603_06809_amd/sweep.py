@@ -6,7 +6,8 @@ are timed as graph launches on one GPU and set side by side.
 
     python -m paper_1603_06809_amd.sweep [--iters 100] [--markdown]
 
-Columns: bytes moved by each schedule and their ratio, time per broadcast,
+Columns: bytes moved by each schedule and their ratio, the messages that would
+cross a node boundary under the paper's blocked placement (24 per node), time per broadcast,
 tuned/native time ratio, and the paper's "bandwidth" figure - message bytes
 per second of one broadcast, in MB/s with MB = 2**20 [Sec. V].  The paper's
 protocol is a barrier followed by 100 iterations; here that is a stream
@@ -34,6 +35,8 @@ def main() -> int:
     ap.add_argument("--iters", type=int, default=100)
     ap.add_argument("--markdown", action="store_true")
     ap.add_argument("--ring-executor", choices=["chains", "steps"], default="chains")
+    ap.add_argument("--ranks-per-node", type=int, default=24,
+                    help="block size of the placement used for the inter-node census")
     args = ap.parse_args()
 
     import torch
@@ -65,7 +68,10 @@ def main() -> int:
             torch.cuda.synchronize()
             us = (time.perf_counter() - t0) / args.iters * 1e6
             info = plan.info()
-            rec[algo] = {"us": round(us, 2), "bytes_moved": int(info.bytes_moved),
+            cen = plan.census(args.ranks_per_node)
+            rec[algo] = {"inter_node_msgs": cen["scatter_inter_msgs"] + cen["ring_inter_msgs"],
+                         "inter_node_bytes": cen["scatter_inter_bytes"] + cen["ring_inter_bytes"],
+                         "us": round(us, 2), "bytes_moved": int(info.bytes_moved),
                          "MBps": round(n / (us * 1e-6) / 2**20, 1),
                          "hbm_gbs": round(2.0 * info.bytes_moved / (us * 1e-6) / 1e9, 1)}
             plan.destroy()
@@ -79,11 +85,12 @@ def main() -> int:
         if not args.markdown:
             print(json.dumps(rec), flush=True)
     if args.markdown:
-        print("| experiment | P | n | bytes tuned/native | native us | tuned us | time tuned/native | "
-              "native MB/s | tuned MB/s | tuned HBM GB/s | ok |")
-        print("|---|---|---|---|---|---|---|---|---|---|---|")
+        print("| experiment | P | n | bytes tuned/native | inter-node msgs native | tuned | native us | "
+              "tuned us | time tuned/native | native MB/s | tuned MB/s | tuned HBM GB/s | ok |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
         for r in rows:
-            print(f"| {r['experiment']} | {r['P']} | {r['n']} | {r['bytes_ratio']} | {r['native']['us']} | "
+            print(f"| {r['experiment']} | {r['P']} | {r['n']} | {r['bytes_ratio']} | "
+                  f"{r['native']['inter_node_msgs']} | {r['tuned']['inter_node_msgs']} | {r['native']['us']} | "
                   f"{r['tuned']['us']} | {r['time_ratio']} | {r['native']['MBps']} | {r['tuned']['MBps']} | "
                   f"{r['tuned']['hbm_gbs']} | {r['ok']} |")
     return 0 if all(r["ok"] for r in rows) else 1

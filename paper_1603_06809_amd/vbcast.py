@@ -33,7 +33,7 @@ SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM = range(7)
 EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
-    "bcast_plan_export_tiles", "bcast_plan_destroy", "vbcast_set_tile_bytes",
+    "bcast_plan_export_tiles", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes",
     "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
     "bcast_strerror",
 ]
@@ -49,6 +49,15 @@ class PlanInfo(C.Structure):
         ("bytes_moved", C.c_uint64), ("ring_msgs_issued", C.c_uint64),
         ("pairing_mismatches", C.c_uint64), ("n_tiles", C.c_uint64),
     ]
+
+
+class Census(C.Structure):
+    _fields_ = [(k, C.c_uint64) for k in (
+        "scatter_inter_msgs", "scatter_inter_bytes", "scatter_intra_msgs", "scatter_intra_bytes",
+        "ring_inter_msgs", "ring_inter_bytes", "ring_intra_msgs", "ring_intra_bytes")]
+
+    def as_dict(self) -> dict:
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
 
 
 class VbcastError(RuntimeError):
@@ -86,6 +95,7 @@ def lib():
     L.bcast_plan_export.argtypes = [vp, u64p, u32p, u32p, u64p, u64p, u64p]
     L.bcast_plan_export_desc.argtypes = [vp, u64p, u64p, i32p, i32p, i32p, i32p, i32p]
     L.bcast_plan_export_tiles.argtypes = [vp, C.c_int, u32p, u32p, u32p]
+    L.bcast_plan_census.argtypes = [vp, C.c_int, vp, C.POINTER(Census)]
     L.bcast_plan_destroy.argtypes = [vp]
     L.vbcast_set_tile_bytes.argtypes = [C.c_size_t]
     L.vbcast_set_ring_executor.argtypes = [C.c_int]
@@ -240,6 +250,11 @@ class Plan:
         _check(lib().bcast_plan_export_tiles(self._h, step, C.byref(n), _ptr(row, C.c_uint32),
                                              _ptr(idx, C.c_uint32)))
         return row, idx
+
+    def census(self, ranks_per_node: int, stream=None) -> dict:
+        out = Census()
+        _check(lib().bcast_plan_census(self._h, ranks_per_node, _stream_handle(stream), C.byref(out)))
+        return out.as_dict()
 
     def destroy(self) -> None:
         if self._h:

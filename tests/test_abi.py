@@ -75,6 +75,7 @@ def test_invalid_arguments_are_rejected_without_a_device():
     assert lib.vbcast_set_ring_executor(7) == V.ERR_ARG
     assert lib.vbcast_set_chain_workgroups_per_cu(0) == V.ERR_ARG
     assert lib.bcast_run_timed(None, None, None) == V.ERR_ARG
+    assert lib.bcast_plan_census(None, 24, None, None) == V.ERR_ARG
 
 
 def test_select_algo_matches_the_oracle_rule():

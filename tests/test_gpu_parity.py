@@ -338,6 +338,28 @@ def test_selected_algorithm_runs(V, P, n):
         comm.destroy()
 
 
+@pytest.mark.parametrize("P,root,n,rpn", [(16, 0, 524_288, 24), (64, 17, 999_983, 24), (256, 5, 524_288, 24),
+                                          (129, 128, 12_288, 24), (10, 3, 1000, 4), (50, 0, 77, 7),
+                                          (513, 256, 8192, 24), (64, 0, 100_000, 24)])
+def test_node_census(V, P, root, n, rpn):
+    """Inter-/intra-node census counted on the GPU vs the oracle's, every algorithm."""
+    import torch
+    bufs = [torch.zeros(n + 16, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    comm = V.Comm.from_tensors(bufs)
+    for algo in (O.NATIVE, O.TUNED, O.BINOMIAL, O.SCATTER_RDB):
+        if algo == O.SCATTER_RDB and P & (P - 1):
+            continue
+        plan = V.bcast_plan(comm, n, 1, root, algo)
+        want = O.node_census(O.build_schedule(P, root, n, algo), rpn)
+        assert plan.census(rpn) == want, (P, root, n, rpn, algo)
+        plan.destroy()
+    plan = V.bcast_plan(comm, n, 1, root, V.TUNED)
+    with pytest.raises(V.VbcastError):
+        plan.census(0)
+    plan.destroy()
+    comm.destroy()
+
+
 # ------------------------------------------------------------------ the paper's own shapes
 
 PAPER_SHAPES = (
