@@ -402,6 +402,58 @@ def build_schedule(P: int, root: int, n: int, algo: str) -> Schedule:
 
 
 # --------------------------------------------------------------------------
+# the multi-core-aware three-phase broadcast                         [Sec. I]
+#
+# The paper describes it in one sentence and does not implement it: a binomial
+# broadcast inside the root's node, then the scatter-ring-allgather between the
+# nodes, then a binomial broadcast inside every other node.  Readings taken
+# where the sentence is silent: ranks sit on nodes in blocks of
+# ``ranks_per_node`` [Sec. V-A]; a node is represented between the nodes by
+# its lowest rank; the inter-node phase starts from the root node's
+# representative, which holds the message after the first phase.
+# --------------------------------------------------------------------------
+
+@dataclass
+class SubSchedule:
+    phase: int                 # 1, 2 or 3
+    members: List[int]         # absolute ranks of the sub-communicator, in its rank order
+    sched: Schedule            # schedule in the sub-communicator's own rank numbers
+
+    def rows_absolute(self, s: int) -> List[Row]:
+        m = self.members
+        return [(m[a], m[b], off, ln) for (a, b, off, ln) in self.sched.steps[s]]
+
+
+def smp_schedule(P: int, root: int, n: int, ranks_per_node: int, ring_algo: str) -> List[SubSchedule]:
+    """The three phases as schedules over sub-communicators, in execution
+    order: phase 1 (one), phase 2 (one), phase 3 (one per node other than the
+    root's; they are independent of each other)."""
+    if ring_algo not in (NATIVE, TUNED):
+        raise ValueError(ring_algo)
+    if P < 1 or not (0 <= root < P) or ranks_per_node < 1:
+        raise ValueError("bad arguments")
+    nodes = [list(range(a, min(a + ranks_per_node, P))) for a in range(0, P, ranks_per_node)]
+    root_node = root // ranks_per_node
+    out: List[SubSchedule] = []
+    home = nodes[root_node]
+    out.append(SubSchedule(1, home, build_schedule(len(home), home.index(root), n, BINOMIAL)))
+    leaders = [nd[0] for nd in nodes]
+    out.append(SubSchedule(2, leaders, build_schedule(len(leaders), root_node, n, ring_algo)))
+    for j, nd in enumerate(nodes):
+        if j != root_node:
+            out.append(SubSchedule(3, nd, build_schedule(len(nd), 0, n, BINOMIAL)))
+    return out
+
+
+def run_smp(bufs: Sequence[np.ndarray], subs: Sequence[SubSchedule], phases=(1, 2, 3)) -> None:
+    """Execute the sub-schedules of the given phases, in order."""
+    for sub in subs:
+        if sub.phase in phases:
+            for s in range(sub.sched.n_steps):
+                apply_step(bufs, sub.rows_absolute(s))
+
+
+# --------------------------------------------------------------------------
 # inter-node / intra-node census                                  [Sec. V-A]
 # --------------------------------------------------------------------------
 

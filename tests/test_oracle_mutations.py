@@ -11,6 +11,7 @@ import pytest
 import test_oracle_pins as pins
 import test_oracle_mailbox as mailbox
 import test_oracle_mpich_paths as paths
+import test_oracle_smp as smp
 
 SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
                    "oracle", "bcast_oracle.py")
@@ -82,6 +83,14 @@ MUTANTS = {
     "census: ranks dealt round-robin to nodes": (
         'kind = "inter" if src // ranks_per_node != dst // ranks_per_node else "intra"',
         'kind = "inter" if src % ranks_per_node != dst % ranks_per_node else "intra"'),
+    "three-phase: middle phase starts at node 0": (
+        "build_schedule(len(leaders), root_node, n, ring_algo)", "build_schedule(len(leaders), 0, n, ring_algo)"),
+    "three-phase: first phase starts at the node's lowest rank": (
+        "build_schedule(len(home), home.index(root), n, BINOMIAL)", "build_schedule(len(home), 0, n, BINOMIAL)"),
+    "three-phase: nodes represented by their highest rank": (
+        "leaders = [nd[0] for nd in nodes]", "leaders = [nd[-1] for nd in nodes]"),
+    "three-phase: the root's node is broadcast to twice": (
+        "        if j != root_node:\n            out.append(SubSchedule(3,", "        if True:\n            out.append(SubSchedule(3,"),
     "zero-length rows kept": (
         "for (src, dst), (disp, cnt) in sends.items() if cnt > 0]",
         "for (src, dst), (disp, cnt) in sends.items()]"),
@@ -134,6 +143,8 @@ def run_pin_suite():
     pins.test_node_census_closed_forms(64, 17, 999_983, 24)
     pins.test_node_census_closed_forms(10, 3, 1000, 4)
     pins.test_node_census_paper_sizes()
+    for case in [(9, 4, 5, 4), (17, 16, 12_288, 4), (25, 12, 5, 24), (7, 6, 5, 3)]:
+        smp.test_three_phases(*case)
 
 
 def test_unmutated_oracle_passes_the_compact_suite():
@@ -147,6 +158,7 @@ def test_pins_reject_mutant(name, monkeypatch):
     monkeypatch.setattr(pins, "O", mutant)
     monkeypatch.setattr(mailbox, "O", mutant)
     monkeypatch.setattr(paths, "O", mutant)
+    monkeypatch.setattr(smp, "O", mutant)
     with pytest.raises(BaseException) as info:
         run_pin_suite()
     assert not isinstance(info.value, (KeyboardInterrupt, SystemExit))
