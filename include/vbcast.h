@@ -244,6 +244,42 @@ int bcast_plan_census(const vbcast_plan *plan, int ranks_per_node, void *hip_str
 int bcast_plan_destroy(vbcast_plan *plan);
 
 /*
+ * The multi-core-aware broadcast the paper describes for medium messages on a
+ * non-power-of-two process count [Sec. I]: (1) a binomial broadcast among the
+ * ranks of the root's node, (2) the scatter-ring-allgather among one rank per
+ * node, (3) a binomial broadcast inside every other node.  The paper describes
+ * it in one sentence and does not implement it; where that sentence is silent:
+ * ranks sit on nodes in blocks of ranks_per_node [Sec. V-A], a node's
+ * representative is its lowest rank, and phase 2 starts from the root node's
+ * representative.  The plan is a sequence of ordinary plans over
+ * sub-communicators (subsets of comm's rank buffers), chained in one graph.
+ *   ring_algo   VBCAST_NATIVE or VBCAST_TUNED for phase 2.
+ * Errors: ARG (null, ranks_per_node < 1, other ring_algo), ROOT, COUNT, HIP, NOMEM.
+ */
+typedef struct vbcast_smp_plan vbcast_smp_plan;
+int bcast_plan_smp(const vbcast_comm *comm, size_t count, size_t dtype_size, int root,
+                   int ranks_per_node, int ring_algo, void *hip_stream, vbcast_smp_plan **out);
+
+/* Launch the whole three-phase broadcast (one graph) on hip_stream; asynchronous. */
+int bcast_run_smp(const vbcast_smp_plan *plan, void *hip_stream);
+
+/* Run the sub-plans of one phase (1, 2 or 3) as plain launches on hip_stream,
+ * asynchronously; used to look at the state between phases.  ARG for other phases. */
+int bcast_run_smp_phase(const vbcast_smp_plan *plan, int phase, void *hip_stream);
+
+/*
+ * The sub-plans in execution order: *count (host pointer) receives their number
+ * when sub is NULL; otherwise sub-plan `index` is returned in *sub (owned by the
+ * three-phase plan; valid until it is destroyed), its phase in *phase, and the
+ * absolute ranks of its sub-communicator, in that communicator's rank order, in
+ * members[0 .. *n_members) (host array with room for P entries; may be NULL).
+ */
+int bcast_smp_subplan(const vbcast_smp_plan *plan, int index, int *count, const vbcast_plan **sub,
+                      int *phase, int *n_members, int *members);
+
+int bcast_plan_smp_destroy(vbcast_smp_plan *plan);
+
+/*
  * The algorithm MPICH's broadcast takes for nbytes on P processes, as the paper
  * states it [Abstract; Sec. I; thresholds in Sec. V]: short messages (below
  * VBCAST_SHORT_MSG_BYTES) -> VBCAST_BINOMIAL; medium messages on a power-of-two P

@@ -37,6 +37,18 @@ struct vbcast_plan {
     hipGraphExec_t exec = nullptr;
 };
 
+struct vbcast_smp_plan {
+    struct Sub {
+        int phase = 0;
+        std::vector<int> members;       // absolute ranks, in the sub-communicator's order
+        vbcast_comm *comm = nullptr;
+        vbcast_plan *plan = nullptr;
+    };
+    std::vector<Sub> subs;              // execution order
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
 namespace {
 
 thread_local std::string g_hip_msg;
@@ -544,6 +556,132 @@ int bcast_plan_census(const vbcast_plan *plan, int ranks_per_node, void *hip_str
             out->ring_intra_bytes += v[3];
         }
     }
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_smp_destroy(vbcast_smp_plan *plan) {
+    if (!plan) return VBCAST_ERR_ARG;
+    if (plan->exec) (void)hipGraphExecDestroy(plan->exec);
+    if (plan->graph) (void)hipGraphDestroy(plan->graph);
+    for (auto &sub : plan->subs) {
+        if (sub.plan) (void)bcast_plan_destroy(sub.plan);
+        if (sub.comm) (void)vbcast_comm_destroy(sub.comm);
+    }
+    delete plan;
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_smp(const vbcast_comm *comm, size_t count, size_t dtype_size, int root,
+                   int ranks_per_node, int ring_algo, void *hip_stream, vbcast_smp_plan **out) {
+    if (!out) return VBCAST_ERR_ARG;
+    *out = nullptr;
+    if (!comm || ranks_per_node < 1) return VBCAST_ERR_ARG;
+    if (ring_algo != VBCAST_NATIVE && ring_algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
+    const int P = comm->P;
+    if (root < 0 || root >= P) return VBCAST_ERR_ROOT;
+    if (dtype_size != 0 && count > SIZE_MAX / dtype_size) return VBCAST_ERR_COUNT;
+    if ((uint64_t)count * (uint64_t)dtype_size > comm->buf_bytes) return VBCAST_ERR_COUNT;
+
+    vbcast_smp_plan *sp = new (std::nothrow) vbcast_smp_plan;
+    if (!sp) return VBCAST_ERR_NOMEM;
+    const int n_nodes = (P + ranks_per_node - 1) / ranks_per_node;
+    const int root_node = root / ranks_per_node;
+    auto node_ranks = [&](int j) {
+        std::vector<int> m;
+        for (int r = j * ranks_per_node; r < P && r < (j + 1) * ranks_per_node; ++r) m.push_back(r);
+        return m;
+    };
+    int rc = VBCAST_SUCCESS;
+    auto add = [&](int phase, std::vector<int> members, int sub_root, int algo) {
+        if (rc != VBCAST_SUCCESS) return;
+        vbcast_smp_plan::Sub sub;
+        sub.phase = phase;
+        sub.members = std::move(members);
+        std::vector<void *> ptrs;
+        for (int r : sub.members) ptrs.push_back(comm->host_bases[(size_t)r]);
+        rc = vbcast_comm_create((int)ptrs.size(), ptrs.data(), comm->buf_bytes, &sub.comm);
+        if (rc == VBCAST_SUCCESS)
+            rc = bcast_plan(sub.comm, count, dtype_size, sub_root, algo, hip_stream, &sub.plan);
+        sp->subs.push_back(std::move(sub));   // kept even on failure so it is cleaned up
+    };
+    add(1, node_ranks(root_node), root - root_node * ranks_per_node, VBCAST_BINOMIAL);
+    {
+        std::vector<int> leaders;
+        for (int j = 0; j < n_nodes; ++j) leaders.push_back(j * ranks_per_node);
+        add(2, std::move(leaders), root_node, ring_algo);
+    }
+    for (int j = 0; j < n_nodes; ++j)
+        if (j != root_node) add(3, node_ranks(j), 0, VBCAST_BINOMIAL);
+
+    // one graph: every sub-plan's table kernels and steps, in order
+    if (rc == VBCAST_SUCCESS) {
+        hipStream_t cap = nullptr;
+        hipError_t e = hipStreamCreateWithFlags(&cap, hipStreamNonBlocking);
+        if (e != hipSuccess) rc = hip_fail(e, "hipStreamCreateWithFlags");
+        if (rc == VBCAST_SUCCESS) {
+            e = hipStreamBeginCapture(cap, hipStreamCaptureModeRelaxed);
+            if (e != hipSuccess) rc = hip_fail(e, "hipStreamBeginCapture");
+            if (rc == VBCAST_SUCCESS) {
+                for (auto &sub : sp->subs) {
+                    const vbcast_plan *p = sub.plan;
+                    e = vbcast::launch_plan_kernels(p->pa, graph_tile_map_steps(p), cap);
+                    if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
+                    if (rc == VBCAST_SUCCESS)
+                        rc = launch_steps(p, 0, p->pa.n_steps ? p->pa.n_scatter : 0, cap, nullptr);
+                    if (rc == VBCAST_SUCCESS) rc = launch_ring(p, cap);
+                    if (rc != VBCAST_SUCCESS) break;
+                }
+                hipGraph_t graph = nullptr;
+                e = hipStreamEndCapture(cap, &graph);
+                if (rc == VBCAST_SUCCESS && e != hipSuccess) rc = hip_fail(e, "hipStreamEndCapture");
+                sp->graph = graph;
+            }
+            (void)hipStreamDestroy(cap);
+        }
+        if (rc == VBCAST_SUCCESS) {
+            e = hipGraphInstantiate(&sp->exec, sp->graph, nullptr, nullptr, 0);
+            if (e != hipSuccess) rc = hip_fail(e, "hipGraphInstantiate");
+        }
+    }
+    if (rc != VBCAST_SUCCESS) {
+        (void)bcast_plan_smp_destroy(sp);
+        return rc;
+    }
+    *out = sp;
+    return VBCAST_SUCCESS;
+}
+
+int bcast_run_smp(const vbcast_smp_plan *plan, void *hip_stream) {
+    if (!plan || !plan->exec) return VBCAST_ERR_ARG;
+    HIP_TRY(hipGraphLaunch(plan->exec, static_cast<hipStream_t>(hip_stream)));
+    return VBCAST_SUCCESS;
+}
+
+int bcast_run_smp_phase(const vbcast_smp_plan *plan, int phase, void *hip_stream) {
+    if (!plan || phase < 1 || phase > 3) return VBCAST_ERR_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    for (const auto &sub : plan->subs) {
+        if (sub.phase != phase) continue;
+        const vbcast_plan *p = sub.plan;
+        int rc = launch_steps(p, 0, p->pa.n_steps ? p->pa.n_scatter : 0, stream, nullptr);
+        if (rc == VBCAST_SUCCESS) rc = launch_ring(p, stream);
+        if (rc != VBCAST_SUCCESS) return rc;
+    }
+    return VBCAST_SUCCESS;
+}
+
+int bcast_smp_subplan(const vbcast_smp_plan *plan, int index, int *count, const vbcast_plan **sub,
+                      int *phase, int *n_members, int *members) {
+    if (!plan) return VBCAST_ERR_ARG;
+    if (count) *count = (int)plan->subs.size();
+    if (!sub) return count ? VBCAST_SUCCESS : VBCAST_ERR_ARG;
+    if (index < 0 || index >= (int)plan->subs.size()) return VBCAST_ERR_ARG;
+    const auto &s = plan->subs[(size_t)index];
+    *sub = s.plan;
+    if (phase) *phase = s.phase;
+    if (n_members) *n_members = (int)s.members.size();
+    if (members)
+        for (size_t k = 0; k < s.members.size(); ++k) members[k] = s.members[k];
     return VBCAST_SUCCESS;
 }
 

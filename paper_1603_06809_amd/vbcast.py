@@ -35,7 +35,8 @@ EXPORTS = [
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
     "bcast_plan_export_tiles", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes",
     "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
-    "bcast_strerror",
+    "bcast_plan_smp", "bcast_run_smp", "bcast_run_smp_phase", "bcast_smp_subplan",
+    "bcast_plan_smp_destroy", "bcast_strerror",
 ]
 
 
@@ -100,6 +101,11 @@ def lib():
     L.vbcast_set_tile_bytes.argtypes = [C.c_size_t]
     L.vbcast_set_ring_executor.argtypes = [C.c_int]
     L.vbcast_set_chain_workgroups_per_cu.argtypes = [C.c_int]
+    L.bcast_plan_smp.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int, vp, C.POINTER(vp)]
+    L.bcast_run_smp.argtypes = [vp, vp]
+    L.bcast_run_smp_phase.argtypes = [vp, C.c_int, vp]
+    L.bcast_smp_subplan.argtypes = [vp, C.c_int, i32p, C.POINTER(vp), i32p, i32p, i32p]
+    L.bcast_plan_smp_destroy.argtypes = [vp]
     L.vbcast_select_algo.argtypes = [C.c_size_t, C.c_int, C.c_int, C.POINTER(C.c_int)]
     L.bcast_strerror.argtypes = [C.c_int]
     L.bcast_strerror.restype = C.c_char_p
@@ -260,6 +266,50 @@ class Plan:
         if self._h:
             _check(lib().bcast_plan_destroy(self._h))
             self._h = C.c_void_p()
+
+
+class SmpPlan:
+    """vbcast_smp_plan handle: the three-phase multi-core-aware broadcast."""
+
+    def __init__(self, comm: Comm, count: int, dtype_size: int, root: int, ranks_per_node: int,
+                 ring_algo, stream=None):
+        self.comm = comm
+        self._h = C.c_void_p()
+        _check(lib().bcast_plan_smp(comm._h, count, dtype_size, root, ranks_per_node,
+                                    ALGOS.get(ring_algo, ring_algo), _stream_handle(stream),
+                                    C.byref(self._h)))
+
+    def run(self, stream=None) -> None:
+        _check(lib().bcast_run_smp(self._h, _stream_handle(stream)))
+
+    def run_phase(self, phase: int, stream=None) -> None:
+        _check(lib().bcast_run_smp_phase(self._h, phase, _stream_handle(stream)))
+
+    def subplans(self):
+        """[(phase, members, Plan)] in execution order; the Plan objects are views
+        owned by this plan (do not destroy them)."""
+        n = C.c_int()
+        _check(lib().bcast_smp_subplan(self._h, 0, C.byref(n), None, None, None, None))
+        out = []
+        for k in range(n.value):
+            h, phase, nm = C.c_void_p(), C.c_int(), C.c_int()
+            members = np.zeros(self.comm.P, np.int32)
+            _check(lib().bcast_smp_subplan(self._h, k, None, C.byref(h), C.byref(phase), C.byref(nm),
+                                           _ptr(members, C.c_int32)))
+            view = Plan.__new__(Plan)
+            view.comm, view._h = self.comm, h
+            out.append((phase.value, members[: nm.value].tolist(), view))
+        return out
+
+    def destroy(self) -> None:
+        if self._h:
+            _check(lib().bcast_plan_smp_destroy(self._h))
+            self._h = C.c_void_p()
+
+
+def bcast_plan_smp(comm: Comm, count: int, dtype_size: int, root: int, ranks_per_node: int,
+                   ring_algo, stream=None) -> SmpPlan:
+    return SmpPlan(comm, count, dtype_size, root, ranks_per_node, ring_algo, stream)
 
 
 def bcast_plan(comm: Comm, count: int, dtype_size: int, root: int, algo, stream=None) -> Plan:

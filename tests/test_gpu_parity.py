@@ -360,6 +360,45 @@ def test_node_census(V, P, root, n, rpn):
     comm.destroy()
 
 
+SMP_CASES = [(9, 4, 12_288, 4), (17, 16, 100_001, 4), (25, 12, 12_288, 24), (33, 0, 524_287, 8),
+             (65, 40, 1_048_576, 24), (129, 5, 12_288, 24), (129, 128, 524_287, 24), (7, 6, 5, 3),
+             (24, 23, 4096, 24), (1, 0, 100, 24), (10, 3, 0, 4)]
+
+
+@pytest.mark.parametrize("P,root,n,rpn", SMP_CASES)
+def test_three_phase_broadcast(V, P, root, n, rpn):
+    """The multi-core-aware three-phase broadcast [Sec. I]: sub-communicators and
+    their tables exact, state exact at the phase boundaries, graph run exact."""
+    w = I.Workload(f"smp_{P}_{root}_{n}", P, root, n, seed=31_000 + P)
+    state = H.device_buffers(w, pad=40)
+    comm = V.Comm([state[r].data_ptr() for r in range(P)], state.shape[1])
+    for ring in (O.NATIVE, O.TUNED):
+        subs = O.smp_schedule(P, root, n, rpn, ring)
+        plan = V.bcast_plan_smp(comm, n, 1, root, rpn, ring)
+        got = plan.subplans()
+        assert [(ph, m) for (ph, m, _p) in got] == [(s.phase, s.members) for s in subs]
+        for (_ph, _m, view), sub in zip(got, subs):
+            check_tables(view, sub.sched)
+        H.refill(state, w)
+        ref = H.host_buffers(w, pad=40)
+        for phase in (1, 2, 3):
+            plan.run_phase(phase)
+            O.run_smp(ref, subs, phases=(phase,))
+            assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (P, root, n, rpn, ring, phase)
+        H.refill(state, w)
+        plan.run()
+        sync()
+        want = np.stack(O.broadcast_definition(H.host_buffers(w, pad=40), root, n))
+        assert np.array_equal(state.cpu().numpy(), want), (P, root, n, rpn, ring)
+        plan.destroy()
+    for bad in [dict(root=P), dict(rpn=0), dict(ring=V.BINOMIAL)]:
+        args = dict(root=root, rpn=rpn, ring=V.TUNED)
+        args.update(bad)
+        with pytest.raises(V.VbcastError):
+            V.bcast_plan_smp(comm, n, 1, args["root"], args["rpn"], args["ring"])
+    comm.destroy()
+
+
 # ------------------------------------------------------------------ the paper's own shapes
 
 PAPER_SHAPES = (
