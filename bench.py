@@ -36,13 +36,22 @@ MEASURED_TRAFFIC = {
 }
 
 
-def cpu_baseline(w, shrink: int):
-    """The oracle as it stands on a bounded sample: same P and root, message
-    shrunk by `shrink`, tuned schedule, numpy buffers."""
+def mem_available():
+    try:
+        with open("/proc/meminfo") as f:
+            for line in f:
+                if line.startswith("MemAvailable:"):
+                    return int(line.split()[1]) * 1024
+    except OSError:
+        pass
+    return None
+
+
+def time_oracle(w, n):
+    """Run the oracle's tuned schedule for a message of n bytes on numpy buffers."""
     import numpy as np
     from oracle import bcast_oracle as O
 
-    n = max(w.P, w.n // shrink)
     sched = O.build_schedule(w.P, w.root, n, O.TUNED)
     rng = np.random.default_rng(w.seed)
     bufs = [np.zeros(n, dtype=np.uint8) for _ in range(w.P)]
@@ -53,13 +62,32 @@ def cpu_baseline(w, shrink: int):
     O.run_steps(bufs, sched)
     dt = time.perf_counter() - t0
     ok = all(np.array_equal(b, bufs[w.root]) for b in bufs)
+    return sched.bytes_moved, dt, ok
+
+
+def cpu_baseline(w, wanted_shrink: int, budget_s: float = 15.0):
+    """The oracle as it stands, one core, on a bounded sample of the workload:
+    same P and root, tuned schedule, the message shrunk by a power of two chosen
+    so that the host buffers fit in 40 % of the available memory and - judged
+    from a small pilot run - the timed part takes about `budget_s` seconds at
+    most."""
+    pilot_n = max(w.P, w.n // 64)
+    moved, dt, _ = time_oracle(w, pilot_n)
+    rate = moved / dt                                   # bytes moved per second
+    shrink = max(1, wanted_shrink)
+    avail = mem_available()
+    while shrink < 64 and ((avail is not None and w.P * (w.n // shrink) > 0.4 * avail)
+                           or (w.P - 1) * (w.n // shrink) > rate * budget_s):
+        shrink *= 2
+    n = max(w.P, w.n // shrink)
+    moved, dt, ok = (moved, dt, _) if n == pilot_n else time_oracle(w, n)
     return {
-        "value": round(2.0 * sched.bytes_moved / dt / 1e9, 3),
+        "value": round(2.0 * moved / dt / 1e9, 3),
         "unit": "GB/s",
         "cores": 1,
         "kind": "oracle",
-        "sample": f"same P={w.P}, root={w.root}, tuned schedule, message shrunk {shrink}x to "
-                  f"{n} bytes ({sched.bytes_moved} bytes moved in {dt:.2f} s); result "
+        "sample": f"same P={w.P}, root={w.root}, tuned schedule, message shrunk {w.n // n}x to "
+                  f"{n} bytes ({moved} bytes moved in {dt:.2f} s); result "
                   f"{'equals' if ok else 'DIFFERS FROM'} the broadcast definition",
     }
 
@@ -74,7 +102,8 @@ def main() -> int:
     ap.add_argument("--pad", type=int, default=0, help="extra bytes between rank buffers")
     ap.add_argument("--ring-executor", choices=["chains", "steps"], default="chains")
     ap.add_argument("--chain-wgs-per-cu", type=int, default=0)
-    ap.add_argument("--cpu-shrink", type=int, default=8)
+    ap.add_argument("--cpu-shrink", type=int, default=2,
+                    help="the CPU oracle is timed on the same P and root with the message shrunk by this")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--init", choices=["seeded", "fast"], default="seeded",
                     help="fast: poison from one torch random fill (for profiler runs)")
