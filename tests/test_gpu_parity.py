@@ -434,6 +434,74 @@ def test_paper_sweep_shapes(V, P, n):
     comm.destroy()
 
 
+# ------------------------------------------------------------------ random shapes, streams, many ranks
+
+def test_random_shapes_final_state(V):
+    """A seeded random walk over (P, root, n, algorithm): tables and final state."""
+    import random
+    rnd = random.Random(20160306)
+    for _ in range(60):
+        P = rnd.choice([2, 3, 5, 6, 11, 12, 20, 31, 48, 100, 127, 200])
+        root = rnd.randrange(P)
+        n = rnd.choice([rnd.randrange(0, 64), rnd.randrange(64, 20_000), rnd.randrange(20_000, 3_000_000)])
+        algo = rnd.choice([O.NATIVE, O.TUNED, O.TUNED, O.BINOMIAL])
+        w = I.Workload(f"rnd_{P}_{root}_{n}", P, root, n, seed=rnd.randrange(1 << 30))
+        V.vbcast_set_tile_bytes(rnd.choice([4096, 8192, 16384]))
+        try:
+            state, comm, plan = make(V, w, algo, pad=rnd.choice([0, 1, 40, 300]),
+                                     executor=rnd.choice(EXECUTORS))
+        finally:
+            V.vbcast_set_tile_bytes(DEFAULT_TILE)
+        check_tables(plan, O.build_schedule(P, root, n, algo))
+        plan.run()
+        sync()
+        want = np.stack(O.broadcast_definition(
+            [H.host_row(w, r, state.shape[1]) for r in range(P)], root, n))
+        assert np.array_equal(state.cpu().numpy(), want), (P, root, n, algo)
+        plan.destroy()
+        comm.destroy()
+
+
+def test_runs_on_a_side_stream_and_back_to_back(V):
+    """bcast_run on a stream of the caller's choice; two plans on the same
+    buffers one after the other on that stream."""
+    import torch
+    w = I.workload("P24_n4M")
+    state = H.device_buffers(w)
+    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tuned = V.bcast_plan(comm, w.n, 1, w.root, V.TUNED, stream=side)
+        native = V.bcast_plan(comm, w.n, 1, w.root, V.NATIVE, stream=side)
+        V.bcast_run(tuned, stream=side)
+        V.bcast_run(native, stream=side)
+        V.bcast_run(tuned, stream=side)
+    side.synchronize()
+    want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+    assert np.array_equal(state.cpu().numpy(), want)
+    tuned.destroy()
+    native.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("P,n", [(1500, 3000), (2049, 40_000), (1024, 1_000_000)])
+def test_many_ranks(V, P, n):
+    """More ranks than one workgroup has lanes: the table kernels loop and carry."""
+    w = I.Workload(f"many_{P}_{n}", P, P - 7, n, seed=4242 + P)
+    state, comm, plan = make(V, w, O.TUNED, pad=0)
+    sched = O.build_schedule(P, w.root, n, O.TUNED)
+    check_tables(plan, sched)
+    check_desc(plan, w)
+    plan.run()
+    sync()
+    want = np.stack(O.broadcast_definition([H.host_row(w, r, state.shape[1]) for r in range(P)],
+                                           w.root, n))
+    assert np.array_equal(state.cpu().numpy(), want)
+    plan.destroy()
+    comm.destroy()
+
+
 # ------------------------------------------------------------------ the large workload
 
 @pytest.fixture(scope="module")
