@@ -115,7 +115,8 @@ int vbcast_comm_destroy(vbcast_comm *comm);
  * [Sec. III-A Fig. 3 for NATIVE; Sec. IV Figs. 4-5 for TUNED], and for every
  * step the map from copy tiles to rows.  Then record one graph that holds the
  * table-generation kernels followed by the copy kernels.
- *   comm        communicator; must outlive the plan.
+ *   comm        communicator; must outlive the plan.  The device that was current
+ *               when it was created must be current now (ARG otherwise).
  *   count, dtype_size   message = count * dtype_size bytes; 0 is valid.
  *   root        absolute rank in [0, P).
  *   algo        VBCAST_NATIVE, VBCAST_TUNED, VBCAST_BINOMIAL or VBCAST_SCATTER_RDB
@@ -188,7 +189,8 @@ typedef struct vbcast_plan_info {
 int bcast_plan_info(const vbcast_plan *plan, vbcast_plan_info *info);
 
 /*
- * Copy the step tables to the host (synchronous).  Any output may be NULL.
+ * Copy the step tables to the host (synchronous copies; the caller makes sure no
+ * launch of this plan is still running).  Any output may be NULL.
  *   step_ptr    n_steps + 1 entries; rows of step s are [step_ptr[s], step_ptr[s+1])
  *   src, dst    one entry per row: absolute ranks
  *   off, len    one entry per row: byte offset and length

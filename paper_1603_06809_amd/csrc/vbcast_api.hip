@@ -237,6 +237,13 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     const uint64_t tile_cap64 = ((n * per_step) >> tile_log2) + 2ull * (uint64_t)P + 1ull;
     if (tile_cap64 >= (1ull << 31)) return VBCAST_ERR_COUNT;
 
+    {
+        // tables go next to the rank buffers: the communicator's device must be current
+        int dev = -1;
+        hipError_t de = hipGetDevice(&dev);
+        if (de != hipSuccess) return hip_fail(de, "hipGetDevice");
+        if (dev != comm->device) return VBCAST_ERR_ARG;
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     vbcast_plan *plan = new (std::nothrow) vbcast_plan;
     if (!plan) return VBCAST_ERR_NOMEM;
