@@ -161,7 +161,9 @@ int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hi
  * Run the whole broadcast once as plain launches (no graph) with events recorded
  * on hip_stream between its three phases, wait, and write the elapsed
  * milliseconds to phase_ms[0..2] (host array): table generation, scatter levels,
- * ring phase (executed the way the plan's graph executes it).  Synchronous.
+ * the steps after the scatter - executed the way the plan's graph executes them:
+ * with VBCAST_RING_CHAINS the scatter is part of the one launch, so phase_ms[1]
+ * is (close to) 0 and phase_ms[2] covers scatter and ring.  Synchronous.
  * Errors: ARG (null), HIP.
  */
 int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms);
@@ -299,18 +301,21 @@ int vbcast_select_algo(size_t nbytes, int P, int tuned, int *algo);
 int vbcast_set_tile_bytes(size_t tile_bytes);
 
 /*
- * How the graphs of plans created afterwards execute the P-1 ring steps
- * [Sec. III-A: a rank forwards in step i+1 the chunk it received in step i]:
- *   VBCAST_RING_STEPS   one copy kernel per ring step, in step order; every step
- *                       is complete before the next starts.
- *   VBCAST_RING_CHAINS  (default) one launch for the whole ring: every piece of
- *                       every chunk is carried through its P-1 transfers in
- *                       order, independently of the other pieces - the ordering
+ * How the graphs of plans created afterwards execute the scatter levels and the
+ * P-1 ring steps [Sec. III-A: a subtree root passes on part of what it received;
+ * a rank forwards in ring step i+1 the chunk it received in step i]:
+ *   VBCAST_RING_STEPS   one copy kernel per step, in step order; every step is
+ *                       complete before the next starts.
+ *   VBCAST_RING_CHAINS  (default) one launch for the scatter and the ring together:
+ *                       every piece of every chunk is carried down its path in the
+ *                       scatter tree and then through its P-1 ring transfers, in
+ *                       order and independently of the other pieces - the ordering
  *                       MPI's blocking point-to-point calls impose, without a
  *                       barrier between steps.  The same rows are copied, source
  *                       to destination through memory, and the final state is
  *                       the same; there is no global "state after step i" while
- *                       it runs.
+ *                       it runs.  (Applies to VBCAST_NATIVE and VBCAST_TUNED; the
+ *                       other algorithms always run step by step.)
  * bcast_run_steps always runs whole steps.  Process-wide; ARG for other values.
  */
 int vbcast_set_ring_executor(int mode);

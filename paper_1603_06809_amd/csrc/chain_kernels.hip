@@ -1,4 +1,4 @@
-// Ring phase executed in dependency order by one launch.
+// Scatter and ring executed in dependency order by one launch.
 //
 // In the ring a chunk travels: the chunk with relative index c starts at the
 // rank that holds it after the scatter and in ring step i is passed from
@@ -8,24 +8,34 @@
 // all the ordering MPI's blocking calls impose; there is no barrier between
 // ring steps in the paper's code either [Sec. IV, listing].  The tuned ring
 // drops some transfers of a chain (the receiver already holds the chunk from
-// the scatter); the chain then continues from that receiver's copy.
+// the scatter); the chain then continues from that receiver's copy.  The
+// scatter is the same kind of chain: chunk c goes down the binomial tree from
+// the root to rank c, one hop at every level whose distance bit is set in c
+// [Sec. III-A, Figs. 1-2], and every rank that holds the chunk "from the
+// scatter" got it from this very chain.  So the whole broadcast splits into
+// independent chains, one per piece of a chunk, each starting in the root's
+// buffer.
 //
 // (Chunks at least a tile long; shorter chunks take the per-wavefront kernel at
-// the end of this file.)  The message space [0, n) is cut into tile-aligned slabs.  A workgroup takes a
-// slab and walks it through all P - 1 ring steps: in step i it copies the slab's
-// part of each chunk from the step's source rank to its destination rank (the
-// same rows the step tables hold, looked up in the chunk-major "chain" view the
-// plan writes next to them), then fences and goes on with step i + 1, whose
-// source is what it has just written.  Every lane re-reads from memory exactly
-// the words it wrote one step earlier; the data is still in this XCD's L2, so
-// the only traffic that has to reach HBM is the write of every rank's copy.
-// The resident workgroups together hold (workgroups x tile) bytes in flight,
-// sized to stay inside the L2s; a workgroup that finishes a slab takes the next
-// one a whole grid further on, so all workgroups do the same amount of work.
+// the end of this file.)  The message space [0, n) is cut into tile-aligned
+// slabs.  A workgroup takes a slab and walks it through all scatter levels and
+// ring steps: in a step it copies the slab's part of each chunk from the step's
+// source rank to its destination rank (the same rows the step tables hold,
+// looked up in the chunk-major "chain" view the plan writes next to them), then
+// fences and goes on with the next step, whose source is what it has just
+// written.  Every lane re-reads from memory exactly the words it wrote one step
+// earlier; they are still in the compute unit's write-through L1 (or the XCD's
+// L2), so the only traffic that has to reach HBM is the write of every rank's
+// copy.  The resident workgroups together hold (workgroups x tile) bytes in
+// flight, sized so that a compute unit's share fits its L1; a workgroup that
+// finishes a slab takes the next one a whole grid further on, so all workgroups
+// do the same amount of work.
 //
 // Between two steps a workgroup-scope fence orders the stores of one step
-// before the loads of the next.  Wider scopes are not needed and are costly
-// here: an agent-scope acquire invalidates the whole L2 of the XCD.
+// before the loads of the next: writer and reader of every byte are the same
+// lane, and all wavefronts of a workgroup share one L1 (the code is not built
+// for threadgroup-split mode).  Wider scopes are not needed and are costly here:
+// an agent-scope acquire invalidates the whole L2 of the XCD.
 
 #include "vbcast_internal.h"
 
@@ -44,16 +54,17 @@ __device__ __forceinline__ void step_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }
 
-// chain[c * (P - 1) + (i - 1)]: destination buffer of chunk c's transfer in ring
-// step i; bit 0 set = the step's table has no such row (dropped or empty).
+// chain[c * (L + P - 1) + s]: the buffer that holds chunk c after step s (scatter
+// levels first, then ring steps); bit 0 set = step s has no row for this chunk
+// (not on its tree path at that level, dropped by the tuned ring, or empty).
 template <int TILE_LOG2>
 __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restrict__ chain,
                                                        const uint64_t *__restrict__ chunk_off,
                                                        uint8_t *const *__restrict__ bases, int P,
-                                                       int root, uint64_t n, uint64_t ss,
+                                                       int L, int root, uint64_t n, uint64_t ss,
                                                        uint32_t n_slabs) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
-    const size_t hops = (size_t)P - 1;
+    const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
     // Workgroups are handed to the XCDs round-robin (workgroup id mod 8).  Give
     // each XCD one contiguous run of slabs per pass instead of every eighth slab,
     // so that the addresses one XCD touches spread over all of its L2 channels.
@@ -70,9 +81,7 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
             constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
             const uint32_t lane_off = threadIdx.x * 16u;
             const uint64_t *ch = chain + (size_t)c0 * hops;
-            int r = c0 + root;
-            if (r >= P) r -= P;
-            const uint8_t *src = bases[r] + lo;
+            const uint8_t *src = bases[root] + lo;   // every chunk starts in the root's buffer
             uint64_t e = ch[0];
             for (size_t i = 1; i <= hops; ++i) {
                 const uint64_t nxt = ch[i < hops ? i : 0];  // next step's entry, early
@@ -102,12 +111,8 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
             const uint64_t cut = c1 > c0 ? chunk_off[c1] : hi;   // A = [lo, cut), B = [cut, hi)
             const uint64_t *chA = chain + (size_t)c0 * hops;
             const uint64_t *chB = chain + (size_t)c1 * hops;
-            int rA = c0 + root;
-            if (rA >= P) rA -= P;
-            int rB = c1 + root;
-            if (rB >= P) rB -= P;
-            const uint8_t *srcA = bases[rA];
-            const uint8_t *srcB = bases[rB];
+            const uint8_t *srcA = bases[root];
+            const uint8_t *srcB = bases[root];
 
             uint64_t word_at[PER_LANE];
             bool word_a[PER_LANE], word_b[PER_LANE];
@@ -171,8 +176,8 @@ template <int LANES>
 __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__restrict__ chain,
                                                              const uint64_t *__restrict__ chunk_off,
                                                              uint8_t *const *__restrict__ bases,
-                                                             int P, int root) {
-    const size_t hops = (size_t)P - 1;
+                                                             int P, int L, int root) {
+    const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
     const int c = (int)(blockIdx.x * (kThreads / LANES) + (threadIdx.x / LANES));
     if (c >= P) return;
     const uint32_t lane = threadIdx.x % LANES;
@@ -188,9 +193,7 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
     const uint32_t words = (uint32_t)((tail - body) >> 4);
 
     const uint64_t *ch = chain + (size_t)c * hops;
-    int r = c + root;
-    if (r >= P) r -= P;
-    const uint8_t *src = bases[r];
+    const uint8_t *src = bases[root];
     uint64_t e = ch[0];
     for (size_t i = 1; i <= hops; ++i) {
         const uint64_t nxt = ch[i < hops ? i : 0];
@@ -235,12 +238,12 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hi
         // chunks shorter than 4 KiB: one workgroup, or one wavefront, per chunk
         if (pa.ss > 1024) {
             hipLaunchKernelGGL(ring_chain_small<kThreads>, dim3((uint32_t)pa.P), dim3(kThreads), 0,
-                               stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.root);
+                               stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.L, pa.root);
         } else {
             const uint32_t per_wg = kThreads / 64;
             hipLaunchKernelGGL(ring_chain_small<64>, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
                                dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P,
-                               pa.root);
+                               pa.L, pa.root);
         }
         return hipGetLastError();
     }
@@ -252,7 +255,7 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hi
     const dim3 g(grid), b(kThreads);
 #define VB_LAUNCH(TL)                                                                       \
     hipLaunchKernelGGL(ring_chain<TL>, g, b, 0, stream, pa.chain, pa.chunk_off, pa.bases,   \
-                       pa.P, pa.root, pa.n, pa.ss, n_slabs)
+                       pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs)
     switch (tl) {
         case 12: VB_LAUNCH(12); break;
         case 13: VB_LAUNCH(13); break;

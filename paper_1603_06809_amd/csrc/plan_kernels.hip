@@ -151,8 +151,9 @@ __global__ __launch_bounds__(kThreads) void plan_descriptors(PlanArrays pa) {
 // its right neighbour.  NATIVE posts every such send.  TUNED posts it while
 // the sender's step <= P - i and afterwards only if the sender's tail is
 // send-only; the receiver decides symmetrically from its own (step, flag), and
-// the two decisions are compared (they always agree).  Every ring decision is
-// also written into the chunk-major chain view used by the one-launch ring.
+// the two decisions are compared (they always agree).  Every scatter and ring
+// decision is also written into the chunk-major chain view used by the
+// one-launch executor.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
     __shared__ uint32_t slots32[kWaves];
@@ -229,14 +230,27 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
             }
         }
         const bool valid = posted && len > 0;
+        const size_t chain_stride = (size_t)pa.L + (size_t)P - 1;
         if (kind == RING && rho < P) {
             // the same decision, filed under the chunk instead of the step
             int c = rho + 1 - i;
             if (c < 0) c += P;
             int dst = dst_rel + pa.root;
             if (dst >= P) dst -= P;
-            pa.chain[(size_t)c * (P - 1) + (i - 1)] =
+            pa.chain[(size_t)c * chain_stride + (size_t)s] =
                 reinterpret_cast<uint64_t>(pa.bases[dst]) | (valid ? 0ull : 1ull);
+        }
+        if (kind == SCATTER && rho < P && pa.algo <= 1) {
+            // The scatter level seen from chunk c = rho: the message of the subtree root
+            // (c with its low bits cleared) to that root + m carries this chunk iff bit
+            // m of c is set; after the level the chunk sits at c with the bits below m
+            // cleared.
+            const int c = rho;
+            const bool moves = (c & m) != 0 && pa.chunk_len[c] > 0;
+            int holder = (c & ~(m - 1)) + pa.root;
+            if (holder >= P) holder -= P;
+            pa.chain[(size_t)c * chain_stride + (size_t)s] =
+                reinterpret_cast<uint64_t>(pa.bases[holder]) | (moves ? 0ull : 1ull);
         }
         uint32_t tiles_here = 0;
         if (valid) tiles_here = (uint32_t)(((off + len - 1) >> tl) - (off >> tl)) + 1u;

@@ -99,12 +99,25 @@ int launch_steps(const vbcast_plan *plan, int first, int last, hipStream_t strea
     return VBCAST_SUCCESS;
 }
 
-// The steps after the scatter, the way the plan's graph runs them.
+bool one_launch(const vbcast_plan *plan) {
+    const int a = plan->pa.algo;
+    return (a == VBCAST_NATIVE || a == VBCAST_TUNED) && plan->ring_executor == VBCAST_RING_CHAINS;
+}
+
+// The scatter levels, the way the plan's graph runs them: step by step, or not at
+// all when the one-launch executor carries them together with the ring.
+int launch_scatter(const vbcast_plan *plan, hipStream_t stream) {
+    const PlanArrays &pa = plan->pa;
+    if (pa.n_steps == 0 || one_launch(plan)) return VBCAST_SUCCESS;
+    return launch_steps(plan, 0, pa.n_scatter, stream, nullptr);
+}
+
+// The steps after the scatter (with the one-launch executor: all steps), the way
+// the plan's graph runs them.
 int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
-    const bool ring_algo = pa.algo == VBCAST_NATIVE || pa.algo == VBCAST_TUNED;
-    if (ring_algo && plan->ring_executor == VBCAST_RING_CHAINS) {
+    if (one_launch(plan)) {
         hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, stream);
         if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
         return VBCAST_SUCCESS;
@@ -115,8 +128,7 @@ int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
 int graph_tile_map_steps(const vbcast_plan *plan) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return 0;
-    const bool ring_algo = pa.algo == VBCAST_NATIVE || pa.algo == VBCAST_TUNED;
-    return ring_algo && plan->ring_executor == VBCAST_RING_CHAINS ? pa.n_scatter : pa.n_steps;
+    return one_launch(plan) ? 0 : pa.n_steps;
 }
 
 int build_graph(vbcast_plan *plan) {
@@ -129,11 +141,11 @@ int build_graph(vbcast_plan *plan) {
         return hip_fail(e, "hipStreamBeginCapture");
     }
     const PlanArrays &pa = plan->pa;
-    // The one-launch ring reads the chain view, not tile maps: inside the graph
-    // only the scatter levels need theirs rebuilt.
+    // The one-launch executor reads the chain view, not tile maps: its graph does
+    // not rebuild them (they were built at plan time for bcast_run_steps).
     e = vbcast::launch_plan_kernels(pa, graph_tile_map_steps(plan), cap);
     if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
-    if (rc == VBCAST_SUCCESS) rc = launch_steps(plan, 0, pa.n_steps ? pa.n_scatter : 0, cap, nullptr);
+    if (rc == VBCAST_SUCCESS) rc = launch_scatter(plan, cap);
     if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, cap);
     hipGraph_t graph = nullptr;
     e = hipStreamEndCapture(cap, &graph);
@@ -273,7 +285,8 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     const size_t o_sw_step = lay.take(sizeof(int32_t) * Pz);
     const size_t o_sw_flag = lay.take(sizeof(int32_t) * Pz);
     const size_t o_rows = lay.take(sizeof(Row) * S * Pz);
-    const size_t o_chain = lay.take(ring_algo ? sizeof(uint64_t) * Pz * (Pz - 1) : 0);
+    const size_t o_chain =
+        lay.take(ring_algo ? sizeof(uint64_t) * Pz * ((size_t)ceil_log2_int(P) + Pz - 1) : 0);
     const size_t o_tile_ptr = lay.take(sizeof(uint32_t) * S * (Pz + 1));
     const size_t o_tiles = lay.take(sizeof(Tile) * S * (size_t)pa.tile_cap);
     const size_t o_step_rows = lay.take(sizeof(uint32_t) * S);
@@ -431,7 +444,7 @@ int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms) 
     }
     mark(1);
     if (rc == VBCAST_SUCCESS)
-        rc = launch_steps(plan, 0, plan->pa.n_steps ? plan->pa.n_scatter : 0, stream, nullptr);
+        rc = launch_scatter(plan, stream);
     mark(2);
     if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, stream);
     mark(3);
@@ -633,8 +646,7 @@ int bcast_plan_smp(const vbcast_comm *comm, size_t count, size_t dtype_size, int
                     const vbcast_plan *p = sub.plan;
                     e = vbcast::launch_plan_kernels(p->pa, graph_tile_map_steps(p), cap);
                     if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
-                    if (rc == VBCAST_SUCCESS)
-                        rc = launch_steps(p, 0, p->pa.n_steps ? p->pa.n_scatter : 0, cap, nullptr);
+                    if (rc == VBCAST_SUCCESS) rc = launch_scatter(p, cap);
                     if (rc == VBCAST_SUCCESS) rc = launch_ring(p, cap);
                     if (rc != VBCAST_SUCCESS) break;
                 }
@@ -670,7 +682,7 @@ int bcast_run_smp_phase(const vbcast_smp_plan *plan, int phase, void *hip_stream
     for (const auto &sub : plan->subs) {
         if (sub.phase != phase) continue;
         const vbcast_plan *p = sub.plan;
-        int rc = launch_steps(p, 0, p->pa.n_steps ? p->pa.n_scatter : 0, stream, nullptr);
+        int rc = launch_scatter(p, stream);
         if (rc == VBCAST_SUCCESS) rc = launch_ring(p, stream);
         if (rc != VBCAST_SUCCESS) return rc;
     }

@@ -42,8 +42,10 @@ struct PlanArrays {
     uint8_t *const *bases;  // [P] rank buffers, by absolute rank
 
     Row *rows;            // [n_steps][P]
-    uint64_t *chain;      // [P][P - 1] chunk-major view of the ring rows: destination
-                          // buffer of chunk c in ring step i, bit 0 set = no such row
+    uint64_t *chain;      // [P][L + P - 1] chunk-major view of the scatter and ring rows
+                          // (ring algorithms only): entry s of chunk c = the buffer
+                          // that holds the chunk after step s, bit 0 set = the step's
+                          // table has no row for this chunk (nothing is copied)
     uint32_t *tile_ptr;   // [n_steps][P + 1] exclusive scan of tiles per row
     Tile *tiles;          // [n_steps][tile_cap]
 
@@ -85,8 +87,8 @@ hipError_t launch_plan_census(const PlanArrays &pa, int ranks_per_node, hipStrea
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
                             uint32_t n_tiles, int tile_log2, hipStream_t stream);
 
-// Enqueue the ring phase as one launch that walks every slab of the message
-// through all ring steps.  `wgs_at_plan_tile` persistent workgroups would share
+// Enqueue the whole scatter + ring broadcast as one launch that walks every slab
+// of the message through all scatter levels and ring steps.  `wgs_at_plan_tile` persistent workgroups would share
 // the slabs at the plan's tile size; the launch may pick a smaller slab (and
 // proportionally more workgroups) or one wavefront per chunk for short chunks.
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream);
