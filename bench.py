@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs (profiles/), scaled by what the same counters read for a plain
 # copy of known size.  Valid only for the configuration it was measured on.
 MEASURED_TRAFFIC = {
-    ("P513_n128M", "chains", 8192, 2): None,      # to be re-measured for the one-launch executor
+    ("P513_n128M", "chains", 8192, 2): 70.50e9,   # ring_chain: 1.65 GB read + 68.85 GB written
     ("P513_n128M", "steps", 8192, 2): 268.2e6,    # step_copy, one ring step: 134.2 MB + 134.0 MB
 }
 
