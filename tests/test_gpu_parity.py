@@ -502,6 +502,51 @@ def test_many_ranks(V, P, n):
     comm.destroy()
 
 
+def test_largest_communicator(V):
+    """VBCAST_MAX_RANKS ranks: too many rows for the oracle's Python loops to list in
+    a test, so the counts are held to the closed forms the oracle is pinned to
+    (bytes (P-1) n, messages P (P-1) minus the subtree savings, log2 P tree
+    levels) and the final state to the definition of broadcast."""
+    import torch
+    P, n, root = 8192, 100_003, 8000
+    w = I.Workload("max_ranks", P, root, n, seed=8192)
+    stride = H.stride_of(n, 0)
+    state = torch.zeros((P, stride), dtype=torch.uint8, device="cuda")
+    msg = I.message_torch(w, "cuda")
+    state[root, :n].copy_(msg)
+    comm = V.Comm([state[r].data_ptr() for r in range(P)], stride)
+    ss = -(-n // P)
+    clen = [max(0, min(ss, n - c * ss)) for c in range(P)]
+    span = lambda c: P if c == 0 else min(c & -c, P - c)
+    scatter_bytes = sum(bin(c).count("1") * clen[c] for c in range(P))
+    for algo, ex in ((V.TUNED, "chains"), (V.NATIVE, "chains"), (V.TUNED, "steps")):
+        set_executor(V, ex)
+        plan = V.bcast_plan(comm, n, 1, root, algo)
+        set_executor(V, "chains")
+        i = plan.info()
+        assert (i.n_scatter_steps, i.n_steps, i.ss) == (13, 13 + P - 1, ss)
+        assert i.scatter_bytes == scatter_bytes and i.pairing_mismatches == 0
+        if algo == V.TUNED:
+            assert i.bytes_moved == (P - 1) * n
+        else:
+            assert i.ring_bytes == (P - 1) * n and i.bytes_moved == (P - 1) * n + scatter_bytes
+        # messages: empty chunks are never sent, so count the non-empty ones only
+        if algo == V.NATIVE:
+            empty = sum(1 for c in range(P) if clen[c] == 0)
+            assert i.ring_msgs_issued == P * (P - 1)
+            assert i.ring_rows == (P - empty) * (P - 1)
+        else:
+            assert i.ring_msgs_issued == P * (P - 1) - sum(span(c) - 1 for c in range(P))
+        state.zero_()
+        state[root, :n].copy_(msg)
+        plan.run()
+        sync()
+        assert bool((state[:, :n] == msg).all()), (algo, ex)
+        assert bool((state[:, n:] == 0).all())
+        plan.destroy()
+    comm.destroy()
+
+
 # ------------------------------------------------------------------ the large workload
 
 @pytest.fixture(scope="module")
