@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs (profiles/), scaled by what the same counters read for a plain
 # copy of known size.  Valid only for the configuration it was measured on.
 MEASURED_TRAFFIC = {
-    ("P513_n128M", "chains", 8192, 2): 70.50e9,   # ring_chain: 1.65 GB read + 68.85 GB written
-    ("P513_n128M", "steps", 8192, 2): 268.2e6,    # step_copy, one ring step: 134.2 MB + 134.0 MB
+    ("P513_n128M", "chains", 8192, 2): 70.42e9,   # ring_chain (slab 8 KiB): 1.58 GB read + 68.84 GB written
+    ("P513_n128M", "steps", 16384, 2): 268.4e6,   # step_copy (tile 16 KiB), a full ring step: 134.2 + 134.2 MB
 }
 
 
@@ -98,7 +98,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="P513_n128M")
-    ap.add_argument("--tile-bytes", type=int, default=0, help="copy tile size (0 = library default)")
+    ap.add_argument("--tile-bytes", type=int, default=0,
+                    help="copy tile of the per-step executor (0 = library default)")
+    ap.add_argument("--slab-bytes", type=int, default=0,
+                    help="slab of the one-launch executor (0 = library default)")
     ap.add_argument("--pad", type=int, default=0, help="extra bytes between rank buffers")
     ap.add_argument("--ring-executor", choices=["chains", "steps"], default="chains")
     ap.add_argument("--chain-wgs-per-cu", type=int, default=0)
@@ -125,6 +128,8 @@ def main() -> int:
     V.lib()
     if args.tile_bytes:
         V.vbcast_set_tile_bytes(args.tile_bytes)
+    if args.slab_bytes:
+        V.vbcast_set_chain_slab_bytes(args.slab_bytes)
     if args.chain_wgs_per_cu:
         V.vbcast_set_chain_workgroups_per_cu(args.chain_wgs_per_cu)
     V.vbcast_set_ring_executor(V.RING_CHAINS if args.ring_executor == "chains" else V.RING_STEPS)
@@ -210,8 +215,8 @@ def main() -> int:
             alg_bytes = 2.0 * float(ring_bytes.sum()) / launches
             kernel = "step_copy (one launch per ring step, tuned)"
         achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, int(info.tile_bytes),
-                                        args.chain_wgs_per_cu or 2))
+        size_key = (args.slab_bytes or 8192) if args.ring_executor == "chains" else int(info.tile_bytes)
+        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, size_key, args.chain_wgs_per_cu or 2))
         if args.pad:
             traffic = None
         roof = {
@@ -242,6 +247,7 @@ def main() -> int:
                         "seeded uniform random bytes; step = one tuned broadcast "
                         "(table generation + scatter + ring, one graph launch)",
             "tile_bytes": int(info.tile_bytes),
+            "slab_bytes": args.slab_bytes or 8192,
             "ring_executor": args.ring_executor,
             "rank_stride_bytes": stride,
         },

@@ -295,10 +295,18 @@ int bcast_plan_smp_destroy(vbcast_smp_plan *plan);
 int vbcast_select_algo(size_t nbytes, int P, int tuned, int *algo);
 
 /*
- * Copy-tile size used by plans created afterwards: a power of two between 4096
- * and 65536 bytes (default 8192).  Process-wide; returns ARG for other values.
+ * Copy-tile size of the per-step executor (and of the tile maps) used by plans
+ * created afterwards: a power of two between 4096 and 65536 bytes (default
+ * 16384).  Process-wide; returns ARG for other values.
  */
 int vbcast_set_tile_bytes(size_t tile_bytes);
+
+/*
+ * Slab size of the one-launch executor (VBCAST_RING_CHAINS) for plans created
+ * afterwards: a power of two between 4096 and 65536 bytes (default 8192).  The
+ * launch uses a smaller slab when chunks are shorter than this.  Process-wide.
+ */
+int vbcast_set_chain_slab_bytes(size_t slab_bytes);
 
 /*
  * How the graphs of plans created afterwards execute the scatter levels and the
@@ -321,7 +329,7 @@ int vbcast_set_tile_bytes(size_t tile_bytes);
 int vbcast_set_ring_executor(int mode);
 
 /* Resident workgroups per compute unit for VBCAST_RING_CHAINS (1..16, default 2);
- * together with the tile size this sets how many bytes are in flight at once. */
+ * together with the slab size this sets how many bytes are in flight at once. */
 int vbcast_set_chain_workgroups_per_cu(int k);
 
 /* Text for an error code; never NULL.  The pointer is valid until the calling

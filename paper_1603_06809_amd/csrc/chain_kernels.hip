@@ -225,10 +225,10 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
 
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream) {
     if (pa.n == 0 || pa.P < 2) return hipSuccess;
-    // Slab size: the plan's tile, halved until a slab cannot hold more than one
+    // Slab size: the plan's slab size, halved until a slab cannot hold more than one
     // chunk boundary (slab <= chunk size), but not below 4 KiB; the number of
     // workgroups grows accordingly so the bytes in flight stay the same.
-    int tl = pa.tile_log2;
+    int tl = pa.slab_log2;
     uint64_t grid64 = wgs_at_plan_tile;
     while (tl > 12 && (1ull << tl) > pa.ss) {
         --tl;

@@ -10,7 +10,10 @@
 // buffer, so every tile except a row's first and last is a whole, aligned
 // window; one workgroup of 256 lanes copies one tile.  Consecutive lanes touch
 // consecutive 16-byte words (one wavefront = 1 KiB contiguous per access), and
-// a lane issues all its loads before its first store.
+// a lane issues all its loads before its first store.  Loads are non-temporal:
+// within a launch nothing is read twice, and keeping the read stream from
+// claiming L2 lines made the launch 9-11 % faster; non-temporal stores made it
+// slower and are not used.
 
 #include "vbcast_internal.h"
 
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ ro
         gmem_u32x4 *d = gmem_words(dst + lo);
         u32x4 v[PER_LANE];
 #pragma unroll
-        for (int k = 0; k < PER_LANE; ++k) v[k] = s[tid + k * kThreads];
+        for (int k = 0; k < PER_LANE; ++k) v[k] = __builtin_nontemporal_load(&s[tid + k * kThreads]);
 #pragma unroll
         for (int k = 0; k < PER_LANE; ++k) d[tid + k * kThreads] = v[k];
         return;
@@ -76,13 +79,15 @@ __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ ro
     const uint32_t words = (uint32_t)((tail - body) >> 4);
     uint32_t w = tid;
     for (; w + 3 * kThreads < words; w += 4 * kThreads) {
-        const u32x4 a = s[w], b = s[w + kThreads], c = s[w + 2 * kThreads], e = s[w + 3 * kThreads];
+        const u32x4 a = __builtin_nontemporal_load(&s[w]), b = __builtin_nontemporal_load(&s[w + kThreads]),
+                    c = __builtin_nontemporal_load(&s[w + 2 * kThreads]),
+                    e = __builtin_nontemporal_load(&s[w + 3 * kThreads]);
         d[w] = a;
         d[w + kThreads] = b;
         d[w + 2 * kThreads] = c;
         d[w + 3 * kThreads] = e;
     }
-    for (; w < words; w += kThreads) d[w] = s[w];
+    for (; w < words; w += kThreads) d[w] = __builtin_nontemporal_load(&s[w]);
 }
 
 }  // namespace

@@ -53,7 +53,8 @@ namespace {
 
 thread_local std::string g_hip_msg;
 thread_local std::string g_text;
-std::atomic<int> g_tile_log2{13};
+std::atomic<int> g_tile_log2{14};
+std::atomic<int> g_slab_log2{13};
 std::atomic<int> g_ring_executor{VBCAST_RING_CHAINS};
 std::atomic<int> g_chain_wgs_per_cu{2};
 
@@ -181,6 +182,15 @@ int vbcast_set_tile_bytes(size_t tile_bytes) {
     return VBCAST_ERR_ARG;
 }
 
+int vbcast_set_chain_slab_bytes(size_t slab_bytes) {
+    for (int k = 12; k <= 16; ++k)
+        if (slab_bytes == (size_t(1) << k)) {
+            g_slab_log2.store(k);
+            return VBCAST_SUCCESS;
+        }
+    return VBCAST_ERR_ARG;
+}
+
 int vbcast_set_ring_executor(int mode) {
     if (mode != VBCAST_RING_STEPS && mode != VBCAST_RING_CHAINS) return VBCAST_ERR_ARG;
     g_ring_executor.store(mode);
@@ -271,6 +281,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
                  : algo == VBCAST_SCATTER_RDB ? 2 * pa.L
                                               : pa.L + P - 1;
     pa.tile_log2 = tile_log2;
+    pa.slab_log2 = g_slab_log2.load();
     pa.tile_cap = (uint32_t)tile_cap64;
     pa.n = n;
     pa.ss = (n + (uint64_t)P - 1) / (uint64_t)P;

@@ -31,7 +31,8 @@ struct PlanArrays {
     int32_t L;          // ceil(log2 P)
     int32_t n_scatter;  // scatter steps: L, or 0 for the binomial broadcast
     int32_t n_steps;    // all steps (0 when P == 1)
-    int32_t tile_log2;
+    int32_t tile_log2;  // copy tile of the per-step executor (tile maps)
+    int32_t slab_log2;  // slab of the one-launch executor
     uint32_t tile_cap;  // tile slots per step
     uint64_t n, ss;
 
@@ -89,7 +90,7 @@ hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *
 
 // Enqueue the whole scatter + ring broadcast as one launch that walks every slab
 // of the message through all scatter levels and ring steps.  `wgs_at_plan_tile` persistent workgroups would share
-// the slabs at the plan's tile size; the launch may pick a smaller slab (and
+// the slabs at the plan's slab size; the launch may pick a smaller slab (and
 // proportionally more workgroups) or one wavefront per chunk for short chunks.
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream);
 

@@ -33,7 +33,7 @@ SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM = range(7)
 EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
-    "bcast_plan_export_tiles", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes",
+    "bcast_plan_export_tiles", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
     "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
     "bcast_plan_smp", "bcast_run_smp", "bcast_run_smp_phase", "bcast_smp_subplan",
     "bcast_plan_smp_destroy", "bcast_strerror",
@@ -99,6 +99,7 @@ def lib():
     L.bcast_plan_census.argtypes = [vp, C.c_int, vp, C.POINTER(Census)]
     L.bcast_plan_destroy.argtypes = [vp]
     L.vbcast_set_tile_bytes.argtypes = [C.c_size_t]
+    L.vbcast_set_chain_slab_bytes.argtypes = [C.c_size_t]
     L.vbcast_set_ring_executor.argtypes = [C.c_int]
     L.vbcast_set_chain_workgroups_per_cu.argtypes = [C.c_int]
     L.bcast_plan_smp.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int, vp, C.POINTER(vp)]
@@ -140,6 +141,10 @@ def _stream_handle(stream) -> Optional[int]:
 
 def vbcast_set_tile_bytes(tile_bytes: int) -> None:
     _check(lib().vbcast_set_tile_bytes(tile_bytes))
+
+
+def vbcast_set_chain_slab_bytes(slab_bytes: int) -> None:
+    _check(lib().vbcast_set_chain_slab_bytes(slab_bytes))
 
 
 def vbcast_set_ring_executor(mode: int) -> None:

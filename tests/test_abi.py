@@ -71,7 +71,9 @@ def test_invalid_arguments_are_rejected_without_a_device():
     assert lib.bcast_plan_destroy(None) == V.ERR_ARG
     assert lib.vbcast_set_tile_bytes(1000) == V.ERR_ARG
     assert lib.vbcast_set_tile_bytes(1 << 20) == V.ERR_ARG
-    assert lib.vbcast_set_tile_bytes(8192) == V.SUCCESS
+    assert lib.vbcast_set_tile_bytes(16384) == V.SUCCESS
+    assert lib.vbcast_set_chain_slab_bytes(3000) == V.ERR_ARG
+    assert lib.vbcast_set_chain_slab_bytes(8192) == V.SUCCESS
     assert lib.vbcast_set_ring_executor(7) == V.ERR_ARG
     assert lib.vbcast_set_chain_workgroups_per_cu(0) == V.ERR_ARG
     assert lib.bcast_run_timed(None, None, None) == V.ERR_ARG

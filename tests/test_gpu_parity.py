@@ -12,7 +12,8 @@ import harness as H
 pytestmark = pytest.mark.gpu
 
 ALGOS = [O.NATIVE, O.TUNED]
-DEFAULT_TILE = 8192
+DEFAULT_TILE = 16384
+DEFAULT_SLAB = 8192
 
 
 @pytest.fixture(scope="module")
@@ -22,6 +23,7 @@ def V():
     from paper_1603_06809_amd import vbcast
     vbcast.lib()
     vbcast.vbcast_set_tile_bytes(DEFAULT_TILE)
+    vbcast.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
     vbcast.vbcast_set_ring_executor(vbcast.RING_CHAINS)
     return vbcast
 
@@ -212,10 +214,11 @@ def test_graph_run_final_state(V, name, algo, executor):
     comm.destroy()
 
 
-@pytest.mark.parametrize("tile", [4096, 16384, 32768, 65536])
+@pytest.mark.parametrize("tile", [4096, 8192, 32768, 65536])
 def test_other_tile_sizes(V, tile):
     w = I.workload("P24_n4M")
     V.vbcast_set_tile_bytes(tile)
+    V.vbcast_set_chain_slab_bytes(tile)
     try:
         for algo in ALGOS:
             state, comm, plan = make(V, w, algo)
@@ -238,6 +241,7 @@ def test_other_tile_sizes(V, tile):
             comm.destroy()
     finally:
         V.vbcast_set_tile_bytes(DEFAULT_TILE)
+        V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
 
 
 def test_timed_steps_report_a_time_per_step(V):
@@ -447,11 +451,13 @@ def test_random_shapes_final_state(V):
         algo = rnd.choice([O.NATIVE, O.TUNED, O.TUNED, O.BINOMIAL])
         w = I.Workload(f"rnd_{P}_{root}_{n}", P, root, n, seed=rnd.randrange(1 << 30))
         V.vbcast_set_tile_bytes(rnd.choice([4096, 8192, 16384]))
+        V.vbcast_set_chain_slab_bytes(rnd.choice([4096, 8192, 16384, 65536]))
         try:
             state, comm, plan = make(V, w, algo, pad=rnd.choice([0, 1, 40, 300]),
                                      executor=rnd.choice(EXECUTORS))
         finally:
             V.vbcast_set_tile_bytes(DEFAULT_TILE)
+            V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
         check_tables(plan, O.build_schedule(P, root, n, algo))
         plan.run()
         sync()
