@@ -11,3 +11,11 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def library_is_built():
+    """Tests load the library that is built; only if there is none do they build it."""
+    from paper_1603_06809_amd import build as B
+    if not os.path.exists(B.LIB):
+        B.build_library()
