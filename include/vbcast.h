@@ -226,6 +226,19 @@ int bcast_plan_export_desc(const vbcast_plan *plan, uint64_t *chunk_off, uint64_
 int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles,
                             uint32_t *tile_row, uint32_t *tile_idx);
 
+/*
+ * Copy the chunk-major "chain" view to the host (VBCAST_NATIVE / VBCAST_TUNED
+ * plans only; ARG otherwise): for the chunk with relative index c and step s,
+ * holder[c * n_steps + s] is the absolute rank whose buffer holds the chunk
+ * after step s on the chunk's own path (down the scatter tree, then round the
+ * ring), and moves[c * n_steps + s] is 1 if step s has a row that copies the
+ * chunk there, 0 if not (the chunk is not on a tree edge at that level, the
+ * tuned ring dropped the transfer, or the chunk is empty).  This is the table
+ * the one-launch executor walks.  Arrays need P * n_steps entries; either may be
+ * NULL.  Synchronous.
+ */
+int bcast_plan_export_chain(const vbcast_plan *plan, int32_t *holder, uint8_t *moves);
+
 typedef struct vbcast_census {
     uint64_t scatter_inter_msgs, scatter_inter_bytes; /* scatter rows between nodes   */
     uint64_t scatter_intra_msgs, scatter_intra_bytes; /* scatter rows inside a node   */

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 using vbcast::PlanArrays;
@@ -556,6 +557,27 @@ int bcast_plan_export_tiles(const vbcast_plan *plan, int step, uint32_t *n_tiles
             if (tile_row) tile_row[k] = tmp[k].row;
             if (tile_idx) tile_idx[k] = tmp[k].idx;
         }
+    }
+    return VBCAST_SUCCESS;
+}
+
+int bcast_plan_export_chain(const vbcast_plan *plan, int32_t *holder, uint8_t *moves) {
+    if (!plan) return VBCAST_ERR_ARG;
+    const PlanArrays &pa = plan->pa;
+    if (pa.algo != VBCAST_NATIVE && pa.algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
+    const size_t entries = (size_t)pa.P * (size_t)pa.n_steps;
+    if (entries == 0 || (!holder && !moves)) return VBCAST_SUCCESS;
+    std::vector<uint64_t> raw(entries);
+    HIP_TRY(hipMemcpy(raw.data(), pa.chain, entries * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    std::unordered_map<uint64_t, int32_t> rank_of;
+    for (int r = 0; r < pa.P; ++r)
+        rank_of[reinterpret_cast<uint64_t>(plan->comm->host_bases[(size_t)r])] = r;
+    for (size_t k = 0; k < entries; ++k) {
+        if (holder) {
+            auto it = rank_of.find(raw[k] & ~15ull);
+            holder[k] = it == rank_of.end() ? -1 : it->second;
+        }
+        if (moves) moves[k] = (raw[k] & 1ull) ? 0 : 1;
     }
     return VBCAST_SUCCESS;
 }

@@ -33,7 +33,7 @@ SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM = range(7)
 EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
-    "bcast_plan_export_tiles", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
+    "bcast_plan_export_tiles", "bcast_plan_export_chain", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
     "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
     "bcast_plan_smp", "bcast_run_smp", "bcast_run_smp_phase", "bcast_smp_subplan",
     "bcast_plan_smp_destroy", "bcast_strerror",
@@ -96,6 +96,7 @@ def lib():
     L.bcast_plan_export.argtypes = [vp, u64p, u32p, u32p, u64p, u64p, u64p]
     L.bcast_plan_export_desc.argtypes = [vp, u64p, u64p, i32p, i32p, i32p, i32p, i32p]
     L.bcast_plan_export_tiles.argtypes = [vp, C.c_int, u32p, u32p, u32p]
+    L.bcast_plan_export_chain.argtypes = [vp, i32p, C.POINTER(C.c_uint8)]
     L.bcast_plan_census.argtypes = [vp, C.c_int, vp, C.POINTER(Census)]
     L.bcast_plan_destroy.argtypes = [vp]
     L.vbcast_set_tile_bytes.argtypes = [C.c_size_t]
@@ -261,6 +262,14 @@ class Plan:
         _check(lib().bcast_plan_export_tiles(self._h, step, C.byref(n), _ptr(row, C.c_uint32),
                                              _ptr(idx, C.c_uint32)))
         return row, idx
+
+    def export_chain(self):
+        """(holder, moves) as [P, n_steps] arrays; see bcast_plan_export_chain."""
+        i = self.info()
+        holder = np.zeros((i.P, i.n_steps), np.int32)
+        moves = np.zeros((i.P, i.n_steps), np.uint8)
+        _check(lib().bcast_plan_export_chain(self._h, _ptr(holder, C.c_int32), _ptr(moves, C.c_uint8)))
+        return holder, moves
 
     def census(self, ranks_per_node: int, stream=None) -> dict:
         out = Census()

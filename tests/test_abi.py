@@ -78,6 +78,7 @@ def test_invalid_arguments_are_rejected_without_a_device():
     assert lib.vbcast_set_chain_workgroups_per_cu(0) == V.ERR_ARG
     assert lib.bcast_run_timed(None, None, None) == V.ERR_ARG
     assert lib.bcast_plan_census(None, 24, None, None) == V.ERR_ARG
+    assert lib.bcast_plan_export_chain(None, None, None) == V.ERR_ARG
     assert lib.bcast_plan_smp(None, 1, 1, 0, 24, 1, None, C.byref(h)) == V.ERR_ARG
     assert lib.bcast_run_smp(None, None) == V.ERR_ARG
     assert lib.bcast_run_smp_phase(None, 1, None) == V.ERR_ARG

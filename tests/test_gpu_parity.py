@@ -96,6 +96,38 @@ def check_desc(plan, w):
         assert (d["sw_step"][r], d["sw_flag"][r]) == (sw if sw else (-1, -1))
 
 
+def check_chain(plan, sched):
+    """The chunk-major view the one-launch executor walks, against the oracle's
+    rows: a chunk moves in a step iff a row of that step covers it, and then it
+    lands in that row's destination; where it does not move it stays with its
+    holder during the scatter, and in ring step i it is looked for at the rank i
+    places above its own."""
+    P, root, n = sched.P, sched.root, sched.n
+    holder, moves = plan.export_chain()
+    ss = sched.ss
+    want_h = np.zeros((P, sched.n_steps), np.int32)
+    want_m = np.zeros((P, sched.n_steps), np.uint8)
+    cur = [root] * P
+    for s, rows in enumerate(sched.steps):
+        landed = {}
+        for (_src, dst, off, ln) in rows:
+            for c in range(off // ss, (off + ln + ss - 1) // ss):
+                landed[c] = dst
+        for c in range(P):
+            if c in landed:
+                cur[c] = landed[c]
+                want_m[c, s] = 1
+            elif s >= sched.n_scatter_steps:
+                cur[c] = (root + c + (s - sched.n_scatter_steps + 1)) % P
+            elif O.chunk_extent(c, n, P)[1] == 0:
+                # an empty chunk still has a place in the tree; nothing is copied for it
+                m = O.ceil_pow2(P) >> (s + 1)
+                cur[c] = (root + (c & ~(m - 1))) % P
+            want_h[c, s] = cur[c]
+    assert np.array_equal(moves, want_m)
+    assert np.array_equal(holder, want_h)
+
+
 def check_tiles(plan, t, steps):
     tb = plan.info().tile_bytes
     for s in steps:
@@ -126,6 +158,7 @@ def test_edge_cases_every_step(V, algo):
         sched = O.build_schedule(P, root, n, algo)
         check_tables(plan, sched)
         check_desc(plan, w)
+        check_chain(plan, sched)
         ref = H.host_buffers(w, pad=40)
         for s in range(sched.n_steps):
             plan.run_steps(s, s + 1)
@@ -157,6 +190,7 @@ def test_state_after_every_step(V, name, algo):
     sched = O.build_schedule(w.P, w.root, w.n, algo)
     t = check_tables(plan, sched)
     check_desc(plan, w)
+    check_chain(plan, sched)
     check_tiles(plan, t, range(sched.n_steps))
     ref = H.host_buffers(w)
     for s in range(sched.n_steps):
@@ -572,6 +606,7 @@ def test_large_workload_tables(V, big, algo):
     sched = O.build_schedule(w.P, w.root, w.n, algo)
     t = check_tables(plan, sched)
     check_desc(plan, w)
+    check_chain(plan, sched)
     check_tiles(plan, t, [0, 9, 10, sched.n_steps - 1])
     plan.destroy()
     comm.destroy()
