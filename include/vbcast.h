@@ -317,7 +317,9 @@ int vbcast_set_tile_bytes(size_t tile_bytes);
 /*
  * Slab size of the one-launch executor (VBCAST_RING_CHAINS) for plans created
  * afterwards: a power of two between 4096 and 65536 bytes (default 8192).  The
- * launch uses a smaller slab when chunks are shorter than this.  Process-wide.
+ * launch uses a smaller slab (down to 1024 bytes) when chunks are shorter than
+ * this, and down to 4096 bytes when the message has fewer slabs than there are
+ * resident workgroups.  Process-wide; returns ARG for other values.
  */
 int vbcast_set_chain_slab_bytes(size_t slab_bytes);
 

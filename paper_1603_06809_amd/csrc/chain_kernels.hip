@@ -16,8 +16,8 @@
 // independent chains, one per piece of a chunk, each starting in the root's
 // buffer.
 //
-// (Chunks at least a tile long; shorter chunks take the per-wavefront kernel at
-// the end of this file.)  The message space [0, n) is cut into tile-aligned
+// (Chunks of at least 1 KiB; shorter ones take the per-wavefront kernel at the
+// end of this file.)  The message space [0, n) is cut into tile-aligned
 // slabs.  A workgroup takes a slab and walks it through all scatter levels and
 // ring steps: in a step it copies the slab's part of each chunk from the step's
 // source rank to its destination rank (the same rows the step tables hold,
@@ -44,6 +44,8 @@ namespace vbcast {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kMinSlabLog2 = 10;   // smallest slab: one wavefront, one word per lane
+constexpr int kFillSlabLog2 = 12;  // slabs are not made smaller than this just to get more of them
 
 __device__ __forceinline__ void step_fence() {
     // Writer and reader of every byte are in the same workgroup (in fact the
@@ -57,8 +59,8 @@ __device__ __forceinline__ void step_fence() {
 // chain[c * (L + P - 1) + s]: the buffer that holds chunk c after step s (scatter
 // levels first, then ring steps); bit 0 set = step s has no row for this chunk
 // (not on its tree path at that level, dropped by the tuned ring, or empty).
-template <int TILE_LOG2>
-__global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restrict__ chain,
+template <int TILE_LOG2, int THREADS>
+__global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict__ chain,
                                                        const uint64_t *__restrict__ chunk_off,
                                                        uint8_t *const *__restrict__ bases, int P,
                                                        int L, int root, uint64_t n, uint64_t ss,
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
         if (c1 == c0 && hi - lo == TILE) {
             // The common case, a whole tile inside one chunk: every lane owns the
             // same PER_LANE words in every step, only the two buffers change.
-            constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
+            constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t lane_off = threadIdx.x * 16u;
             const uint64_t *ch = chain + (size_t)c0 * hops;
             const uint8_t *src = bases[root] + lo;   // every chunk starts in the root's buffer
@@ -90,10 +92,10 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
                     u32x4 v[PER_LANE];
 #pragma unroll
                     for (int k = 0; k < PER_LANE; ++k)
-                        v[k] = *gmem_words(src + lane_off + k * (kThreads * 16));
+                        v[k] = *gmem_words(src + lane_off + k * (THREADS * 16));
 #pragma unroll
                     for (int k = 0; k < PER_LANE; ++k)
-                        *gmem_words(dst + lane_off + k * (kThreads * 16)) = v[k];
+                        *gmem_words(dst + lane_off + k * (THREADS * 16)) = v[k];
                 }
                 step_fence();
                 src = dst;
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
             // word belongs to.  The word that holds the cut between the chunks and
             // the word that holds the end of the message go byte by byte, one lane
             // per byte (lanes 0-15 and 16-31).
-            constexpr int PER_LANE = (int)(TILE / 16) / kThreads;
+            constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t tid = threadIdx.x;
             const uint64_t cut = c1 > c0 ? chunk_off[c1] : hi;   // A = [lo, cut), B = [cut, hi)
             const uint64_t *chA = chain + (size_t)c0 * hops;
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
             bool word_a[PER_LANE], word_b[PER_LANE];
 #pragma unroll
             for (int k = 0; k < PER_LANE; ++k) {
-                word_at[k] = lo + (uint64_t)(tid + k * kThreads) * 16u;
+                word_at[k] = lo + (uint64_t)(tid + k * THREADS) * 16u;
                 word_a[k] = word_at[k] + 16 <= cut;
                 word_b[k] = word_at[k] >= cut && word_at[k] + 16 <= hi;
             }
@@ -166,21 +168,19 @@ __global__ __launch_bounds__(kThreads) void ring_chain(const uint64_t *__restric
     }
 }
 
-// Small chunks (shorter than the smallest slab): a group of LANES lanes - one
-// wavefront, or the whole workgroup for chunks above 1 KiB - walks a whole chunk
-// through the P - 1 steps.  Groups, and the wavefronts inside a group, are
-// independent: a lane only ever re-reads what it wrote itself.  Lanes 0-15 take
-// the bytes before the first 16-byte boundary, lanes 16-31 the bytes after the
-// last one, and all lanes share the 16-byte words in between.
-template <int LANES>
+// Small chunks (shorter than the smallest slab, 1 KiB): one wavefront walks a
+// whole chunk through all steps, one 16-byte word per lane.  Wavefronts are
+// independent: a lane only ever re-reads what it wrote itself.  Lanes 0-15 also
+// take the bytes before the chunk's first 16-byte boundary, lanes 16-31 the bytes
+// after its last one.
 __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__restrict__ chain,
                                                              const uint64_t *__restrict__ chunk_off,
                                                              uint8_t *const *__restrict__ bases,
                                                              int P, int L, int root) {
     const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
-    const int c = (int)(blockIdx.x * (kThreads / LANES) + (threadIdx.x / LANES));
+    const int c = (int)(blockIdx.x * (kThreads / 64) + (threadIdx.x / 64));
     if (c >= P) return;
-    const uint32_t lane = threadIdx.x % LANES;
+    const uint32_t lane = threadIdx.x % 64;
     const uint64_t a = chunk_off[c], b = chunk_off[c + 1];
     if (a >= b) return;
     uint64_t body = (a + 15) & ~15ull;
@@ -189,8 +189,10 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
     if (tail < body) tail = body;
     const bool head_lane = lane < 16 && lane < (uint32_t)(body - a);
     const bool tail_lane = lane >= 16 && lane < 32 && lane - 16 < (uint32_t)(b - tail);
+    const bool byte_lane = head_lane || tail_lane;
     const uint64_t byte_at = head_lane ? a + lane : tail + (lane - 16);
-    const uint32_t words = (uint32_t)((tail - body) >> 4);
+    const bool word_lane = lane < (uint32_t)((tail - body) >> 4);   // fewer than 64 words
+    const uint64_t word_at = body + (uint64_t)lane * 16u;
 
     const uint64_t *ch = chain + (size_t)c * hops;
     const uint8_t *src = bases[root];
@@ -200,20 +202,11 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
         uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull);
         if (!(e & 1)) {
             uint8_t one = 0;
-            if (head_lane || tail_lane) one = *gmem_bytes(src + byte_at);
-            const gmem_u32x4 *s = gmem_words(src + body);
-            gmem_u32x4 *d = gmem_words(dst + body);
-            uint32_t w = lane;
-            for (; w + 3 * LANES < words; w += 4 * LANES) {
-                const u32x4 x0 = s[w], x1 = s[w + LANES], x2 = s[w + 2 * LANES],
-                            x3 = s[w + 3 * LANES];
-                d[w] = x0;
-                d[w + LANES] = x1;
-                d[w + 2 * LANES] = x2;
-                d[w + 3 * LANES] = x3;
-            }
-            for (; w < words; w += LANES) d[w] = s[w];
-            if (head_lane || tail_lane) *gmem_bytes(dst + byte_at) = one;
+            u32x4 v = {0, 0, 0, 0};
+            if (byte_lane) one = *gmem_bytes(src + byte_at);
+            if (word_lane) v = *gmem_words(src + word_at);
+            if (word_lane) *gmem_words(dst + word_at) = v;
+            if (byte_lane) *gmem_bytes(dst + byte_at) = one;
         }
         step_fence();
         src = dst;
@@ -225,26 +218,25 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
 
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream) {
     if (pa.n == 0 || pa.P < 2) return hipSuccess;
-    // Slab size: the plan's slab size, halved until a slab cannot hold more than one
-    // chunk boundary (slab <= chunk size), but not below 4 KiB; the number of
-    // workgroups grows accordingly so the bytes in flight stay the same.
+    // Slab size: the plan's slab size, halved (with twice the workgroups, so the
+    // bytes in flight stay the same) while a slab is longer than a chunk - it must
+    // not hold more than one chunk boundary - down to 1 KiB, and, down to 4 KiB,
+    // while there are fewer slabs than workgroups: a medium message is then spread
+    // over more compute units, each step of its chains moving less per workgroup.
     int tl = pa.slab_log2;
     uint64_t grid64 = wgs_at_plan_tile;
-    while (tl > 12 && (1ull << tl) > pa.ss) {
+    while (tl > kMinSlabLog2 &&
+           ((1ull << tl) > pa.ss ||
+            (tl > kFillSlabLog2 && ((pa.n + (1ull << tl) - 1) >> tl) < grid64))) {
         --tl;
         grid64 *= 2;
     }
     if ((1ull << tl) > pa.ss) {
-        // chunks shorter than 4 KiB: one workgroup, or one wavefront, per chunk
-        if (pa.ss > 1024) {
-            hipLaunchKernelGGL(ring_chain_small<kThreads>, dim3((uint32_t)pa.P), dim3(kThreads), 0,
-                               stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.L, pa.root);
-        } else {
-            const uint32_t per_wg = kThreads / 64;
-            hipLaunchKernelGGL(ring_chain_small<64>, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
-                               dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P,
-                               pa.L, pa.root);
-        }
+        // chunks shorter than 1 KiB: one wavefront per chunk
+        const uint32_t per_wg = kThreads / 64;
+        hipLaunchKernelGGL(ring_chain_small, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
+                           dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.L,
+                           pa.root);
         return hipGetLastError();
     }
     const uint64_t n_slabs64 = (pa.n + (1ull << tl) - 1) >> tl;
@@ -252,16 +244,19 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hi
     const uint32_t n_slabs = (uint32_t)n_slabs64;
     uint32_t grid = grid64 > n_slabs ? n_slabs : (uint32_t)grid64;
     grid = (grid + 7u) & ~7u;  // whole rounds over the 8 XCDs
-    const dim3 g(grid), b(kThreads);
-#define VB_LAUNCH(TL)                                                                       \
-    hipLaunchKernelGGL(ring_chain<TL>, g, b, 0, stream, pa.chain, pa.chunk_off, pa.bases,   \
-                       pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs)
+    const dim3 g(grid);
+    // one 16-byte word per lane in the two smallest slabs, so fewer lanes there
+#define VB_LAUNCH(TL, LANES)                                                                 \
+    hipLaunchKernelGGL((ring_chain<TL, LANES>), g, dim3(LANES), 0, stream, pa.chain,         \
+                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs)
     switch (tl) {
-        case 12: VB_LAUNCH(12); break;
-        case 13: VB_LAUNCH(13); break;
-        case 14: VB_LAUNCH(14); break;
-        case 15: VB_LAUNCH(15); break;
-        case 16: VB_LAUNCH(16); break;
+        case 10: VB_LAUNCH(10, 64); break;
+        case 11: VB_LAUNCH(11, 128); break;
+        case 12: VB_LAUNCH(12, 256); break;
+        case 13: VB_LAUNCH(13, 256); break;
+        case 14: VB_LAUNCH(14, 256); break;
+        case 15: VB_LAUNCH(15, 256); break;
+        case 16: VB_LAUNCH(16, 256); break;
         default: return hipErrorInvalidValue;
     }
 #undef VB_LAUNCH

@@ -472,6 +472,29 @@ def test_paper_sweep_shapes(V, P, n):
     comm.destroy()
 
 
+@pytest.mark.parametrize("P", [5, 16, 33])
+def test_chunk_sizes_around_the_slab_sizes(V, P):
+    """The one-launch executor picks its slab (1, 2, 4, 8 KiB) and its kernel from
+    the chunk size: chunk sizes one below, at and one above every switch, with a
+    last chunk P - 1 bytes short and with an exact fit."""
+    for ss in (1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8192, 8193):
+        for n in (P * ss, P * ss - (P - 1)):
+            w = I.Workload(f"slab_P{P}_n{n}", P, P - 2, n, seed=99_000 + P + ss)
+            assert -(-n // P) == ss
+            init = H.host_buffers(w)
+            want = np.stack(O.broadcast_definition(init, w.root, w.n))
+            state = H.device_buffers(w)
+            comm = V.Comm([state[r].data_ptr() for r in range(P)], state.shape[1])
+            for algo in ALGOS:
+                plan = V.bcast_plan(comm, n, 1, w.root, algo)
+                H.refill(state, w)
+                plan.run()
+                sync()
+                assert np.array_equal(state.cpu().numpy(), want), (P, n, ss, algo)
+                plan.destroy()
+            comm.destroy()
+
+
 # ------------------------------------------------------------------ random shapes, streams, many ranks
 
 def test_random_shapes_final_state(V):
@@ -522,6 +545,29 @@ def test_runs_on_a_side_stream_and_back_to_back(V):
     assert np.array_equal(state.cpu().numpy(), want)
     tuned.destroy()
     native.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("executor", EXECUTORS)
+@pytest.mark.parametrize("algo", ALGOS)
+def test_graph_replays(V, algo, executor):
+    """The same instantiated graph launched five times, with the harness's own
+    eager work (re-poisoning, copies back to the host) and synchronisations
+    between the launches: every replay must give the state the un-graphed steps
+    give, which is the oracle's."""
+    w = I.workload("P96_n12M_ragged")
+    state, comm, plan = make(V, w, algo, executor=executor)
+    want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+    plan.run_steps(0, plan.info().n_steps)
+    sync()
+    assert np.array_equal(state.cpu().numpy(), want)
+    for replay in range(5):
+        H.refill(state, w)
+        sync()
+        plan.run()
+        sync()
+        assert np.array_equal(state.cpu().numpy(), want), (algo, executor, replay)
+    plan.destroy()
     comm.destroy()
 
 
