@@ -633,6 +633,68 @@ def test_largest_communicator(V):
     comm.destroy()
 
 
+@pytest.mark.parametrize("algo", ALGOS)
+def test_offsets_beyond_4_GiB(V, algo):
+    """Three ranks, a message of 6 GiB and a few bytes: the third chunk starts
+    above 2^32, so offsets, tile and slab indices need their 64 bits.  Too large
+    for host buffers: tables are compared in full; the state after the scatter,
+    after the first ring step and at the end is compared on 8 KiB windows (at the
+    start, around every chunk boundary, around 2^32, around the end of the message
+    and at the end of the buffer) built from the oracle's chunk-ownership form;
+    at the end every rank is also compared with the root on the device."""
+    import torch
+    P, root, n = 3, 1, 6 * 2**30 + 12_345
+    w = I.Workload("beyond_4GiB", P, root, n, seed=4_294_967_296 + 7)
+    state = H.device_buffers(w)
+    stride = state.shape[1]
+    comm = V.Comm([state[r].data_ptr() for r in range(P)], stride)
+    sched = O.build_schedule(P, root, n, algo)
+    ss = sched.ss
+    assert 2 * ss > 2**32
+    marks = [0, ss, 2 * ss, 2**32, n, stride]
+    windows = sorted({(max(0, m - 4096), min(stride, m + 4096)) for m in marks})
+
+    def check(k, where):
+        has = O.ownership_after(sched, k)
+        for r in range(P):
+            for (a, b) in windows:
+                want = I.bytes_numpy(w.seed, r + 1, b - a, start=a)
+                for c in range(P):
+                    d, cnt = O.chunk_extent(c, n, P)
+                    lo, hi = max(a, d), min(b, d + cnt)
+                    if lo < hi and (has[r, c] or r == root):
+                        want[lo - a:hi - a] = I.bytes_numpy(w.seed, 0, hi - lo, start=lo)
+                got = state[r, a:b].cpu().numpy()
+                assert np.array_equal(got, want), (algo, where, r, a)
+
+    plan = V.bcast_plan(comm, n, 1, root, algo)
+    check_tables(plan, sched)
+    check_desc(plan, w)
+    check_chain(plan, sched)
+    nsc, S = sched.n_scatter_steps, sched.n_steps
+    done = 0
+    for stop in (nsc, nsc + 1, S):
+        plan.run_steps(done, stop)
+        done = stop
+        sync()
+        check(stop, f"after step {stop}")
+    plan.destroy()
+    for ex in EXECUTORS:
+        set_executor(V, ex)
+        plan = V.bcast_plan(comm, n, 1, root, algo)
+        set_executor(V, "chains")
+        H.refill(state, w)
+        plan.run()
+        sync()
+        check(S, ex)
+        for r in range(P):
+            assert torch.equal(state[r, :n], state[root, :n]), (algo, ex, r)
+        plan.destroy()
+    comm.destroy()
+    del state
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ the large workload
 
 @pytest.fixture(scope="module")
