@@ -149,6 +149,21 @@ int bcast_run(const vbcast_plan *plan, void *hip_stream);
 int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stream);
 
 /*
+ * Steps [first, last) executed by the kernel of the one-launch executor
+ * (VBCAST_RING_CHAINS) in a single launch on hip_stream, asynchronously: every
+ * piece of every chunk is carried through the transfers the tables hold for it
+ * in those steps, in order [Sec. III-A: a rank passes on what it received one
+ * step earlier].  The state of the rank buffers after step first - 1 must be in
+ * place (the root's message for first = 0); afterwards they hold the state after
+ * step last - 1, the same as after bcast_run_steps(first, last).  With first = 0
+ * and last = n_steps this is the launch the plan's graph uses.  VBCAST_NATIVE
+ * and VBCAST_TUNED plans only.
+ * Errors: ARG (null, other algorithm, first < 0, first > last, last > n_steps),
+ * HIP.
+ */
+int bcast_run_chain_steps(const vbcast_plan *plan, int first, int last, void *hip_stream);
+
+/*
  * As bcast_run_steps, but brackets every step's kernel with events recorded on
  * hip_stream, waits for the last one and writes the elapsed milliseconds of
  * step first + i to step_ms[i] (host array of last - first floats; 0 for a step

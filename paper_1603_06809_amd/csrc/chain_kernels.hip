@@ -56,6 +56,14 @@ __device__ __forceinline__ void step_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }
 
+// Where a chunk is found before step `first`: in the root's buffer before the
+// first step [Sec. III-A: the scatter starts from the root], else with whoever
+// holds it after step first - 1.
+__device__ __forceinline__ const uint8_t *chain_start(const uint64_t *ch, uint8_t *const *bases,
+                                                      int root, uint32_t first) {
+    return first == 0 ? bases[root] : reinterpret_cast<const uint8_t *>(ch[first - 1] & ~15ull);
+}
+
 // chain[c * (L + P - 1) + s]: the buffer that holds chunk c after step s (scatter
 // levels first, then ring steps); bit 0 set = step s has no row for this chunk
 // (not on its tree path at that level, dropped by the tuned ring, or empty).
@@ -64,7 +72,8 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                                                        const uint64_t *__restrict__ chunk_off,
                                                        uint8_t *const *__restrict__ bases, int P,
                                                        int L, int root, uint64_t n, uint64_t ss,
-                                                       uint32_t n_slabs) {
+                                                       uint32_t n_slabs, uint32_t first_step,
+                                                       uint32_t last_step) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
     // Workgroups are handed to the XCDs round-robin (workgroup id mod 8).  Give
@@ -83,10 +92,10 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t lane_off = threadIdx.x * 16u;
             const uint64_t *ch = chain + (size_t)c0 * hops;
-            const uint8_t *src = bases[root] + lo;   // every chunk starts in the root's buffer
-            uint64_t e = ch[0];
-            for (size_t i = 1; i <= hops; ++i) {
-                const uint64_t nxt = ch[i < hops ? i : 0];  // next step's entry, early
+            const uint8_t *src = chain_start(ch, bases, root, first_step) + lo;
+            uint64_t e = ch[first_step];
+            for (size_t i = first_step + 1; i <= last_step; ++i) {
+                const uint64_t nxt = ch[i < last_step ? i : first_step];  // next step's entry, early
                 uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull) + lo;
                 if (!(e & 1)) {
                     u32x4 v[PER_LANE];
@@ -113,8 +122,8 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             const uint64_t cut = c1 > c0 ? chunk_off[c1] : hi;   // A = [lo, cut), B = [cut, hi)
             const uint64_t *chA = chain + (size_t)c0 * hops;
             const uint64_t *chB = chain + (size_t)c1 * hops;
-            const uint8_t *srcA = bases[root];
-            const uint8_t *srcB = bases[root];
+            const uint8_t *srcA = chain_start(chA, bases, root, first_step);
+            const uint8_t *srcB = chain_start(chB, bases, root, first_step);
 
             uint64_t word_at[PER_LANE];
             bool word_a[PER_LANE], word_b[PER_LANE];
@@ -132,10 +141,10 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             const bool byte_a = byte_lane && byte_at < cut;
             const bool byte_b = byte_lane && byte_at >= cut;
 
-            uint64_t eA = chA[0];
-            uint64_t eB = chB[0];
-            for (size_t i = 1; i <= hops; ++i) {
-                const size_t nx = i < hops ? i : 0;  // the next step's entries, early
+            uint64_t eA = chA[first_step];
+            uint64_t eB = chB[first_step];
+            for (size_t i = first_step + 1; i <= last_step; ++i) {
+                const size_t nx = i < last_step ? i : first_step;  // the next step's entries, early
                 const uint64_t nA = chA[nx];
                 const uint64_t nB = chB[nx];
                 uint8_t *dA = reinterpret_cast<uint8_t *>(eA & ~15ull);
@@ -176,7 +185,8 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
 __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__restrict__ chain,
                                                              const uint64_t *__restrict__ chunk_off,
                                                              uint8_t *const *__restrict__ bases,
-                                                             int P, int L, int root) {
+                                                             int P, int L, int root,
+                                                             uint32_t first_step, uint32_t last_step) {
     const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
     const int c = (int)(blockIdx.x * (kThreads / 64) + (threadIdx.x / 64));
     if (c >= P) return;
@@ -195,10 +205,10 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
     const uint64_t word_at = body + (uint64_t)lane * 16u;
 
     const uint64_t *ch = chain + (size_t)c * hops;
-    const uint8_t *src = bases[root];
-    uint64_t e = ch[0];
-    for (size_t i = 1; i <= hops; ++i) {
-        const uint64_t nxt = ch[i < hops ? i : 0];
+    const uint8_t *src = chain_start(ch, bases, root, first_step);
+    uint64_t e = ch[first_step];
+    for (size_t i = first_step + 1; i <= last_step; ++i) {
+        const uint64_t nxt = ch[i < last_step ? i : first_step];
         uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull);
         if (!(e & 1)) {
             uint8_t one = 0;
@@ -216,8 +226,11 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
 
 }  // namespace
 
-hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream) {
-    if (pa.n == 0 || pa.P < 2) return hipSuccess;
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
+                             int last_step, hipStream_t stream) {
+    if (pa.n == 0 || pa.P < 2 || first_step >= last_step) return hipSuccess;
+    if (first_step < 0 || last_step > pa.n_steps) return hipErrorInvalidValue;
+    const uint32_t s0 = (uint32_t)first_step, s1 = (uint32_t)last_step;
     // Slab size: the plan's slab size, halved (with twice the workgroups, so the
     // bytes in flight stay the same) while a slab is longer than a chunk - it must
     // not hold more than one chunk boundary - down to 1 KiB, and, down to 4 KiB,
@@ -236,7 +249,7 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hi
         const uint32_t per_wg = kThreads / 64;
         hipLaunchKernelGGL(ring_chain_small, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
                            dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.L,
-                           pa.root);
+                           pa.root, s0, s1);
         return hipGetLastError();
     }
     const uint64_t n_slabs64 = (pa.n + (1ull << tl) - 1) >> tl;
@@ -248,7 +261,7 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hi
     // one 16-byte word per lane in the two smallest slabs, so fewer lanes there
 #define VB_LAUNCH(TL, LANES)                                                                 \
     hipLaunchKernelGGL((ring_chain<TL, LANES>), g, dim3(LANES), 0, stream, pa.chain,         \
-                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs)
+                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs, s0, s1)
     switch (tl) {
         case 10: VB_LAUNCH(10, 64); break;
         case 11: VB_LAUNCH(11, 128); break;

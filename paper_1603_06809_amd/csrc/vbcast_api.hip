@@ -120,7 +120,7 @@ int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
     if (one_launch(plan)) {
-        hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, stream);
+        hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, 0, pa.n_steps, stream);
         if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
         return VBCAST_SUCCESS;
     }
@@ -393,6 +393,17 @@ int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stre
     if (!plan) return VBCAST_ERR_ARG;
     if (first < 0 || first > last || last > plan->pa.n_steps) return VBCAST_ERR_ARG;
     return launch_steps(plan, first, last, static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int bcast_run_chain_steps(const vbcast_plan *plan, int first, int last, void *hip_stream) {
+    if (!plan) return VBCAST_ERR_ARG;
+    const PlanArrays &pa = plan->pa;
+    if (pa.algo != VBCAST_NATIVE && pa.algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
+    if (first < 0 || first > last || last > pa.n_steps) return VBCAST_ERR_ARG;
+    hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, first, last,
+                                             static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
+    return VBCAST_SUCCESS;
 }
 
 int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hip_stream,

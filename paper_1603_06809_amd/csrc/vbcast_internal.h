@@ -88,10 +88,12 @@ hipError_t launch_plan_census(const PlanArrays &pa, int ranks_per_node, hipStrea
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
                             uint32_t n_tiles, int tile_log2, hipStream_t stream);
 
-// Enqueue the whole scatter + ring broadcast as one launch that walks every slab
-// of the message through all scatter levels and ring steps.  `wgs_at_plan_tile` persistent workgroups would share
-// the slabs at the plan's slab size; the launch may pick a smaller slab (and
+// Enqueue steps [first_step, last_step) of a scatter + ring broadcast as one
+// launch that walks every slab of the message through those steps (all of them:
+// 0 and pa.n_steps).  `wgs_at_plan_tile` persistent workgroups would share the
+// slabs at the plan's slab size; the launch may pick a smaller slab (and
 // proportionally more workgroups) or one wavefront per chunk for short chunks.
-hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, hipStream_t stream);
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
+                             int last_step, hipStream_t stream);
 
 }  // namespace vbcast

@@ -31,7 +31,7 @@ RING_CHAINS = 1
 SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM = range(7)
 
 EXPORTS = [
-    "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps",
+    "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps", "bcast_run_chain_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
     "bcast_plan_export_tiles", "bcast_plan_export_chain", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
     "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
@@ -90,6 +90,7 @@ def lib():
     L.bcast_plan.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, vp, C.POINTER(vp)]
     L.bcast_run.argtypes = [vp, vp]
     L.bcast_run_steps.argtypes = [vp, C.c_int, C.c_int, vp]
+    L.bcast_run_chain_steps.argtypes = [vp, C.c_int, C.c_int, vp]
     L.bcast_run_steps_timed.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_float)]
     L.bcast_run_timed.argtypes = [vp, vp, C.POINTER(C.c_float)]
     L.bcast_plan_info.argtypes = [vp, C.POINTER(PlanInfo)]
@@ -220,6 +221,9 @@ class Plan:
     def run_steps(self, first: int, last: int, stream=None) -> None:
         _check(lib().bcast_run_steps(self._h, first, last, _stream_handle(stream)))
 
+    def run_chain_steps(self, first: int, last: int, stream=None) -> None:
+        _check(lib().bcast_run_chain_steps(self._h, first, last, _stream_handle(stream)))
+
     def run_steps_timed(self, first: int, last: int, stream=None) -> np.ndarray:
         ms = np.zeros(max(last - first, 0), dtype=np.float32)
         _check(lib().bcast_run_steps_timed(self._h, first, last, _stream_handle(stream),
@@ -338,3 +342,7 @@ def bcast_run(plan: Plan, stream=None) -> None:
 
 def bcast_run_steps(plan: Plan, first: int, last: int, stream=None) -> None:
     plan.run_steps(first, last, stream)
+
+
+def bcast_run_chain_steps(plan: Plan, first: int, last: int, stream=None) -> None:
+    plan.run_chain_steps(first, last, stream)

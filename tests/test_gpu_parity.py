@@ -40,6 +40,12 @@ def sync():
     torch.cuda.synchronize()
 
 
+def stepper(plan, executor):
+    """Runs steps [first, last): one launch per step, or the one-launch executor's
+    kernel held to that range of steps."""
+    return plan.run_steps if executor == "steps" else plan.run_chain_steps
+
+
 def make(V, w, algo, pad=64, executor="chains"):
     state = H.device_buffers(w, pad)
     comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
@@ -159,12 +165,14 @@ def test_edge_cases_every_step(V, algo):
         check_tables(plan, sched)
         check_desc(plan, w)
         check_chain(plan, sched)
-        ref = H.host_buffers(w, pad=40)
-        for s in range(sched.n_steps):
-            plan.run_steps(s, s + 1)
-            O.apply_step(ref, sched.steps[s])
-            got = state.cpu().numpy()
-            assert np.array_equal(got, np.stack(ref)), (P, root, n, algo, s)
+        for ex in EXECUTORS:
+            H.refill(state, w)
+            ref = H.host_buffers(w, pad=40)
+            for s in range(sched.n_steps):
+                stepper(plan, ex)(s, s + 1)
+                O.apply_step(ref, sched.steps[s])
+                got = state.cpu().numpy()
+                assert np.array_equal(got, np.stack(ref)), (P, root, n, algo, ex, s)
         # and the graph from a fresh state, with either ring executor
         want = np.stack(O.broadcast_definition(H.host_buffers(w, pad=40), root, n))
         plan.destroy()
@@ -182,9 +190,12 @@ def test_edge_cases_every_step(V, algo):
 
 # ------------------------------------------------------------------ the workloads
 
+@pytest.mark.parametrize("executor", EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("name", ["P10_n512K", "P24_n4M"])
-def test_state_after_every_step(V, name, algo):
+def test_state_after_every_step(V, name, algo, executor):
+    """State of every rank buffer after every step, with the per-step kernel and
+    with the one-launch executor's kernel held to one step at a time."""
     w = I.workload(name)
     state, comm, plan = make(V, w, algo)
     sched = O.build_schedule(w.P, w.root, w.n, algo)
@@ -194,18 +205,19 @@ def test_state_after_every_step(V, name, algo):
     check_tiles(plan, t, range(sched.n_steps))
     ref = H.host_buffers(w)
     for s in range(sched.n_steps):
-        plan.run_steps(s, s + 1)
+        stepper(plan, executor)(s, s + 1)
         O.apply_step(ref, sched.steps[s])
-        assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (name, algo, s)
+        assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (name, algo, executor, s)
     want = O.broadcast_definition(H.host_buffers(w), w.root, w.n)
     assert np.array_equal(np.stack(ref), np.stack(want))
     plan.destroy()
     comm.destroy()
 
 
+@pytest.mark.parametrize("executor", EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("name", ["P64_n16M", "P96_n12M_ragged"])
-def test_state_at_sampled_steps(V, name, algo):
+def test_state_at_sampled_steps(V, name, algo, executor):
     w = I.workload(name)
     state, comm, plan = make(V, w, algo)
     sched = O.build_schedule(w.P, w.root, w.n, algo)
@@ -217,12 +229,12 @@ def test_state_at_sampled_steps(V, name, algo):
     stops = sorted({1, nsc, nsc + 1, nsc + 2, nsc + (w.P - 1) // 2, S - 1, S})
     done = 0
     for stop in stops:
-        plan.run_steps(done, stop)
+        stepper(plan, executor)(done, stop)
         O.run_steps(ref, sched, done, stop)
         done = stop
         got = state.cpu().numpy()
         for r in range(w.P):
-            assert np.array_equal(got[r], ref[r]), (name, algo, stop, r)
+            assert np.array_equal(got[r], ref[r]), (name, algo, executor, stop, r)
     plan.destroy()
     comm.destroy()
 
@@ -305,10 +317,16 @@ def test_errors_on_device(V):
         assert e.value.code == code
     plan = V.bcast_plan(comm, 256, 1, 0, V.TUNED)
     for (a, b) in [(-1, 2), (3, 2), (0, plan.info().n_steps + 1)]:
-        with pytest.raises(V.VbcastError) as e:
-            plan.run_steps(a, b)
-        assert e.value.code == V.ERR_ARG
+        for run in (plan.run_steps, plan.run_chain_steps):
+            with pytest.raises(V.VbcastError) as e:
+                run(a, b)
+            assert e.value.code == V.ERR_ARG
     plan.destroy()
+    tree = V.bcast_plan(comm, 256, 1, 0, V.BINOMIAL)   # no chains in a tree broadcast
+    with pytest.raises(V.VbcastError) as e:
+        tree.run_chain_steps(0, 1)
+    assert e.value.code == V.ERR_ARG
+    tree.destroy()
     comm.destroy()
 
 
@@ -672,12 +690,14 @@ def test_offsets_beyond_4_GiB(V, algo):
     check_desc(plan, w)
     check_chain(plan, sched)
     nsc, S = sched.n_scatter_steps, sched.n_steps
-    done = 0
-    for stop in (nsc, nsc + 1, S):
-        plan.run_steps(done, stop)
-        done = stop
-        sync()
-        check(stop, f"after step {stop}")
+    for ex in EXECUTORS:
+        H.refill(state, w)
+        done = 0
+        for stop in (nsc, nsc + 1, S):
+            stepper(plan, ex)(done, stop)
+            done = stop
+            sync()
+            check(stop, f"{ex}, after step {stop}")
     plan.destroy()
     for ex in EXECUTORS:
         set_executor(V, ex)
@@ -749,14 +769,16 @@ def test_large_workload_state(V, big, algo):
     nsc, S = sched.n_scatter_steps, sched.n_steps
     ranks = [w.root, (w.root + 1) % w.P, (w.root + 256) % w.P, (w.root + 384) % w.P,
              (w.root - 1) % w.P, 0, 300]
-    done = 0
-    for stop in [nsc, nsc + 1, nsc + 200, S - 1]:
-        plan.run_steps(done, stop)
-        done = stop
-        sync()
-        want = expected_rows(w, sched, stop, ranks, stride)
-        for r in ranks:
-            assert np.array_equal(state[r].cpu().numpy(), want[r]), (algo, stop, r)
+    for ex, stops in (("steps", [nsc, nsc + 1, nsc + 200, S - 1]), ("chains", [3, nsc + 2, S - 3])):
+        H.refill(state, w)
+        done = 0
+        for stop in stops:
+            stepper(plan, ex)(done, stop)
+            done = stop
+            sync()
+            want = expected_rows(w, sched, stop, ranks, stride)
+            for r in ranks:
+                assert np.array_equal(state[r].cpu().numpy(), want[r]), (algo, ex, stop, r)
     plan.destroy()
     # the whole broadcast through the graph, from a fresh state, with either ring executor
     msg = I.message_numpy(w)
