@@ -56,6 +56,17 @@ __device__ __forceinline__ void step_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }
 
+// Waits until every load issued so far has returned.  Loads and stores of a
+// wavefront complete through one in-order counter, so a wait that the compiler
+// places between two stores of a step (it does, when the stores sit in separate
+// conditional blocks) also waits for the first store to be acknowledged by the
+// L2: one more round trip in the step.  Waiting once, right after the step's
+// loads, leaves nothing to wait for between the stores.
+__device__ __forceinline__ void wait_for_loads() {
+    // s_waitcnt vmcnt(0), with the export and LDS/scalar counters left alone
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
 // Where a chunk is found before step `first`: in the root's buffer before the
 // first step [Sec. III-A: the scatter starts from the root], else with whoever
 // holds it after step first - 1.
@@ -161,6 +172,7 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                 const bool byte_on = (byte_a && runA) || (byte_b && runB);
                 uint8_t one = 0;
                 if (byte_on) one = *gmem_bytes((byte_a ? srcA : srcB) + byte_at);
+                wait_for_loads();
 #pragma unroll
                 for (int k = 0; k < PER_LANE; ++k) {
                     uint8_t *d = word_a[k] ? dA : dB;
@@ -188,7 +200,9 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
                                                              int P, int L, int root,
                                                              uint32_t first_step, uint32_t last_step) {
     const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
-    const int c = (int)(blockIdx.x * (kThreads / 64) + (threadIdx.x / 64));
+    // the chunk is the same for all lanes of a wavefront: say so, and its chain
+    // entries come through scalar loads
+    const int c = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kThreads / 64) + (threadIdx.x / 64)));
     if (c >= P) return;
     const uint32_t lane = threadIdx.x % 64;
     const uint64_t a = chunk_off[c], b = chunk_off[c + 1];
@@ -211,10 +225,11 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
         const uint64_t nxt = ch[i < last_step ? i : first_step];
         uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull);
         if (!(e & 1)) {
+            u32x4 v;
             uint8_t one = 0;
-            u32x4 v = {0, 0, 0, 0};
-            if (byte_lane) one = *gmem_bytes(src + byte_at);
             if (word_lane) v = *gmem_words(src + word_at);
+            if (byte_lane) one = *gmem_bytes(src + byte_at);
+            wait_for_loads();
             if (word_lane) *gmem_words(dst + word_at) = v;
             if (byte_lane) *gmem_bytes(dst + byte_at) = one;
         }
