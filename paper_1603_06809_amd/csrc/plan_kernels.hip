@@ -165,8 +165,8 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
     enum { SCATTER, RING, TREE, EXCHANGE };
     int kind;
     if (s < pa.n_scatter) kind = SCATTER;
-    else if (pa.algo == 2) kind = TREE;
-    else if (pa.algo == 3) kind = EXCHANGE;
+    else if (pa.algo == kAlgoBinomial) kind = TREE;
+    else if (pa.algo == kAlgoScatterRdb) kind = EXCHANGE;
     else kind = RING;
     const int m = (kind == SCATTER || kind == TREE) ? (1 << (pa.L - 1 - s)) : 0;  // tree distance
     const int i = s - pa.n_scatter + 1;                                          // ring step
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
                 dst_rel = (rho + 1 < P) ? rho + 1 : 0;
                 off = pa.chunk_off[c];
                 len = pa.chunk_len[c];
-                if (pa.algo == 0) {
+                if (pa.algo == kAlgoNative) {
                     posted = true;
                 } else {
                     int snd = rho + pa.root;
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
             pa.chain[(size_t)c * chain_stride + (size_t)s] =
                 reinterpret_cast<uint64_t>(pa.bases[dst]) | (valid ? 0ull : 1ull);
         }
-        if (kind == SCATTER && rho < P && pa.algo <= 1) {
+        if (kind == SCATTER && rho < P && (pa.algo == kAlgoNative || pa.algo == kAlgoTuned)) {
             // The scatter level seen from chunk c = rho: the message of the subtree root
             // (c with its low bits cleared) to that root + m carries this chunk iff bit
             // m of c is set; after the level the chunk sits at c with the bits below m

@@ -50,6 +50,11 @@ struct vbcast_smp_plan {
     hipGraphExec_t exec = nullptr;
 };
 
+static_assert(vbcast::kAlgoNative == VBCAST_NATIVE && vbcast::kAlgoTuned == VBCAST_TUNED &&
+                  vbcast::kAlgoBinomial == VBCAST_BINOMIAL &&
+                  vbcast::kAlgoScatterRdb == VBCAST_SCATTER_RDB,
+              "kernel-side algorithm codes must match the public header");
+
 namespace {
 
 thread_local std::string g_hip_msg;

@@ -6,6 +6,10 @@
 
 namespace vbcast {
 
+// Algorithm codes as in the public header (VBCAST_NATIVE ... VBCAST_SCATTER_RDB);
+// the host code checks that the two agree.
+enum : int32_t { kAlgoNative = 0, kAlgoTuned = 1, kAlgoBinomial = 2, kAlgoScatterRdb = 3 };
+
 // One transfer of a step: copy `len` bytes at byte offset `off` from rank
 // `src`'s buffer to the same offset in rank `dst`'s buffer.
 struct Row {
