@@ -5,6 +5,13 @@ bytes on 129 processes.  For every point the native and the tuned broadcast
 are timed as graph launches on one GPU and set side by side.
 
     python -m paper_1603_06809_amd.sweep [--iters 100] [--markdown]
+    python -m paper_1603_06809_amd.sweep --selection [--markdown]
+
+``--selection`` times, on 16, 64 and 129 processes and sizes on both sides of
+the two thresholds (12288 and 524288 bytes [Sec. V]), every broadcast algorithm
+the library has - binomial tree, scatter + recursive doubling (power-of-two
+process counts), scatter + ring native and tuned - and marks the one MPICH's
+size / process-count rule selects [Abstract, Sec. I].
 
 Columns: bytes moved by each schedule and their ratio, the messages that would
 cross a node boundary under the paper's blocked placement (24 per node), time per broadcast,
@@ -30,9 +37,56 @@ def points():
     return pts
 
 
+def selection(V, torch, iters: int, markdown: bool) -> int:
+    sizes = [1024, 4096, 12_287, 12_288, 65_536, 262_144, 524_287, 524_288, 2_097_152]
+    names = ["binomial", "scatter_rdb", "native", "tuned"]
+    rows, all_ok = [], True
+    for P in (16, 64, 129):
+        for n in sizes:
+            stride = (n + 255) // 256 * 256
+            bufs = [torch.empty(stride, dtype=torch.uint8, device="cuda") for _ in range(P)]
+            torch.manual_seed(P * 1_000_003 + n)
+            bufs[0].random_()
+            comm = V.Comm([b.data_ptr() for b in bufs], stride)
+            chosen = V.ALGO_NAMES[V.vbcast_select_algo(n, P, True)]
+            rec = {"P": P, "n": n, "selected": chosen}
+            for name in names:
+                if name == "scatter_rdb" and P & (P - 1):
+                    rec[name] = None
+                    continue
+                for b in bufs[1:]:
+                    b.zero_()
+                plan = V.bcast_plan(comm, n, 1, 0, name)
+                for _ in range(3):
+                    V.bcast_run(plan)
+                torch.cuda.synchronize()
+                all_ok &= all(bool(torch.equal(b[:n], bufs[0][:n])) for b in bufs)
+                t0 = time.perf_counter()
+                for _ in range(iters):
+                    V.bcast_run(plan)
+                torch.cuda.synchronize()
+                rec[name] = round((time.perf_counter() - t0) / iters * 1e6, 2)
+                plan.destroy()
+            comm.destroy()
+            del bufs
+            rows.append(rec)
+            if not markdown:
+                print(json.dumps(rec), flush=True)
+    if markdown:
+        print("| P | n | selected | binomial us | scatter + rec. doubling us | scatter + ring native us | tuned us |")
+        print("|---|---|---|---|---|---|---|")
+        for r in rows:
+            cell = lambda k: "-" if r[k] is None else (f"**{r[k]}**" if r["selected"] == k else str(r[k]))
+            print(f"| {r['P']} | {r['n']} | {r['selected']} | {cell('binomial')} | {cell('scatter_rdb')} | "
+                  f"{cell('native')} | {cell('tuned')} |")
+    return 0 if all_ok else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=100)
+    ap.add_argument("--selection", action="store_true",
+                    help="time every algorithm around the two size thresholds instead")
     ap.add_argument("--markdown", action="store_true")
     ap.add_argument("--ring-executor", choices=["chains", "steps"], default="chains")
     ap.add_argument("--ranks-per-node", type=int, default=24,
@@ -48,6 +102,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     V.lib()
     V.vbcast_set_ring_executor(V.RING_CHAINS if args.ring_executor == "chains" else V.RING_STEPS)
+    if args.selection:
+        return selection(V, torch, args.iters, args.markdown)
 
     rows = []
     for (exp, P, n) in points():
