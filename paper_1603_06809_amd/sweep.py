@@ -6,12 +6,15 @@ are timed as graph launches on one GPU and set side by side.
 
     python -m paper_1603_06809_amd.sweep [--iters 100] [--markdown]
     python -m paper_1603_06809_amd.sweep --selection [--markdown]
+    python -m paper_1603_06809_amd.sweep --smp [--ranks-per-node 24] [--markdown]
 
 ``--selection`` times, on 16, 64 and 129 processes and sizes on both sides of
 the two thresholds (12288 and 524288 bytes [Sec. V]), every broadcast algorithm
 the library has - binomial tree, scatter + recursive doubling (power-of-two
 process counts), scatter + ring native and tuned - and marks the one MPICH's
-size / process-count rule selects [Abstract, Sec. I].
+size / process-count rule selects [Abstract, Sec. I].  ``--smp`` sets the flat
+tuned broadcast beside the multi-core-aware three-phase one [Sec. I] under the
+blocked placement [Sec. V-A]: time, and messages and bytes between nodes.
 
 Columns: bytes moved by each schedule and their ratio, the messages that would
 cross a node boundary under the paper's blocked placement (24 per node), time per broadcast,
@@ -82,9 +85,64 @@ def selection(V, torch, iters: int, markdown: bool) -> int:
     return 0 if all_ok else 1
 
 
+def smp(V, torch, iters: int, rpn: int, markdown: bool) -> int:
+    rows, all_ok = [], True
+    for (P, n) in [(48, 1_048_576), (64, 524_288), (64, 4_194_304), (129, 1_048_576), (256, 524_288),
+                   (256, 4_194_304), (256, 30_000_000)]:
+        stride = (n + 255) // 256 * 256
+        bufs = [torch.empty(stride, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        torch.manual_seed(P * 1_000_003 + n)
+        bufs[0].random_()
+        comm = V.Comm([b.data_ptr() for b in bufs], stride)
+        rec = {"P": P, "n": n, "ranks_per_node": rpn}
+        for kind in ("flat", "three_phase"):
+            for b in bufs[1:]:
+                b.zero_()
+            if kind == "flat":
+                plan = V.bcast_plan(comm, n, 1, 0, "tuned")
+                cens = [plan.census(rpn)]
+            else:
+                plan = V.bcast_plan_smp(comm, n, 1, 0, rpn, "tuned")
+                # a sub-plan's ranks are positions in its sub-communicator: only the
+                # second phase (one rank per node) crosses nodes, with every message
+                cens = []
+                for (phase, members, sub) in plan.subplans():
+                    c = sub.census(1 if phase == 2 else len(members))
+                    cens.append(c)
+            for _ in range(3):
+                plan.run()
+            torch.cuda.synchronize()
+            all_ok &= all(bool(torch.equal(b[:n], bufs[0][:n])) for b in bufs)
+            t0 = time.perf_counter()
+            for _ in range(iters):
+                plan.run()
+            torch.cuda.synchronize()
+            rec[kind] = {
+                "us": round((time.perf_counter() - t0) / iters * 1e6, 2),
+                "inter_node_msgs": sum(c["scatter_inter_msgs"] + c["ring_inter_msgs"] for c in cens),
+                "inter_node_bytes": sum(c["scatter_inter_bytes"] + c["ring_inter_bytes"] for c in cens),
+            }
+            plan.destroy()
+        comm.destroy()
+        del bufs
+        rows.append(rec)
+        if not markdown:
+            print(json.dumps(rec), flush=True)
+    if markdown:
+        print("| P | n | flat tuned us | inter-node msgs | inter-node bytes | three-phase us | inter-node msgs | inter-node bytes |")
+        print("|---|---|---|---|---|---|---|---|")
+        for r in rows:
+            f, t = r["flat"], r["three_phase"]
+            print(f"| {r['P']} | {r['n']} | {f['us']} | {f['inter_node_msgs']} | {f['inter_node_bytes']} | "
+                  f"{t['us']} | {t['inter_node_msgs']} | {t['inter_node_bytes']} |")
+    return 0 if all_ok else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=100)
+    ap.add_argument("--smp", action="store_true",
+                    help="flat tuned broadcast against the three-phase one instead")
     ap.add_argument("--selection", action="store_true",
                     help="time every algorithm around the two size thresholds instead")
     ap.add_argument("--markdown", action="store_true")
@@ -104,6 +162,8 @@ def main() -> int:
     V.vbcast_set_ring_executor(V.RING_CHAINS if args.ring_executor == "chains" else V.RING_STEPS)
     if args.selection:
         return selection(V, torch, args.iters, args.markdown)
+    if args.smp:
+        return smp(V, torch, args.iters, args.ranks_per_node, args.markdown)
 
     rows = []
     for (exp, P, n) in points():
