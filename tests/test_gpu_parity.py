@@ -513,6 +513,18 @@ def test_chunk_sizes_around_the_slab_sizes(V, P):
             comm.destroy()
 
 
+def test_sweep_modes_run_and_check_their_results(V, capsys):
+    """The two side sweeps (every algorithm around the size thresholds; flat
+    against three-phase) return 0 only if every broadcast they timed left every
+    rank equal to the root."""
+    import torch
+    from paper_1603_06809_amd import sweep
+    assert sweep.selection(V, torch, 2, True) == 0
+    assert sweep.smp(V, torch, 2, 24, True) == 0
+    out = capsys.readouterr().out
+    assert out.count("\n| ") >= 27 + 7
+
+
 # ------------------------------------------------------------------ random shapes, streams, many ranks
 
 def test_random_shapes_final_state(V):
