@@ -51,8 +51,9 @@ __device__ __forceinline__ void step_fence() {
     // Writer and reader of every byte are in the same workgroup (in fact the
     // same lane), so workgroup scope is the right one: all wavefronts of a
     // workgroup sit behind one L1, which their own stores keep consistent, and
-    // nothing has to be written back or invalidated - the fence only waits for
-    // the stores and keeps the next step's loads behind them.
+    // nothing has to be written back or invalidated.  In this execution mode the
+    // fence emits no instruction; it keeps the compiler from moving the next
+    // step's loads above this step's stores.
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }
 
