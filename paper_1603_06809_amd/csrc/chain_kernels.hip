@@ -84,15 +84,18 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                                                        const uint64_t *__restrict__ chunk_off,
                                                        uint8_t *const *__restrict__ bases, int P,
                                                        int L, int root, uint64_t n, uint64_t ss,
-                                                       uint32_t n_slabs, uint32_t first_step,
-                                                       uint32_t last_step) {
+                                                       uint32_t n_slabs, uint32_t xcd_run,
+                                                       uint32_t first_step, uint32_t last_step) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
     // Workgroups are handed to the XCDs round-robin (workgroup id mod 8).  Give
-    // each XCD one contiguous run of slabs per pass instead of every eighth slab,
-    // so that the addresses one XCD touches spread over all of its L2 channels.
-    const uint32_t W = gridDim.x;  // a multiple of 8
-    const uint32_t first = (blockIdx.x & 7u) * (W >> 3) + (blockIdx.x >> 3);
+    // each XCD runs of `xcd_run` consecutive slabs (64 KiB) instead of every
+    // eighth slab, so that the addresses one XCD touches spread over all of its L2
+    // channels, while the eight XCDs together still sweep one contiguous window.
+    const uint32_t W = gridDim.x;  // a multiple of 8; W / 8 is a multiple of xcd_run
+    const uint32_t in_xcd = blockIdx.x >> 3;
+    const uint32_t first = (in_xcd / xcd_run) * 8u * xcd_run + (blockIdx.x & 7u) * xcd_run +
+                           (in_xcd % xcd_run);
     for (uint32_t slab = first; slab < n_slabs; slab += W) {
         const uint64_t lo = (uint64_t)slab << TILE_LOG2;
         const uint64_t hi = lo + TILE < n ? lo + TILE : n;
@@ -273,11 +276,14 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, in
     const uint32_t n_slabs = (uint32_t)n_slabs64;
     uint32_t grid = grid64 > n_slabs ? n_slabs : (uint32_t)grid64;
     grid = (grid + 7u) & ~7u;  // whole rounds over the 8 XCDs
+    // slabs per XCD run: 64 KiB worth, but a divisor of the workgroups per XCD
+    uint32_t xcd_run = tl < 16 ? (1u << (16 - tl)) : 1u;
+    while ((grid >> 3) % xcd_run != 0) xcd_run >>= 1;
     const dim3 g(grid);
     // one 16-byte word per lane in the two smallest slabs, so fewer lanes there
 #define VB_LAUNCH(TL, LANES)                                                                 \
     hipLaunchKernelGGL((ring_chain<TL, LANES>), g, dim3(LANES), 0, stream, pa.chain,         \
-                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs, s0, s1)
+                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs, xcd_run, s0, s1)
     switch (tl) {
         case 10: VB_LAUNCH(10, 64); break;
         case 11: VB_LAUNCH(11, 128); break;
