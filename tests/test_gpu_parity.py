@@ -545,12 +545,24 @@ def test_random_shapes_final_state(V):
         finally:
             V.vbcast_set_tile_bytes(DEFAULT_TILE)
             V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
-        check_tables(plan, O.build_schedule(P, root, n, algo))
+        sched = O.build_schedule(P, root, n, algo)
+        check_tables(plan, sched)
         plan.run()
         sync()
         want = np.stack(O.broadcast_definition(
             [H.host_row(w, r, state.shape[1]) for r in range(P)], root, n))
         assert np.array_equal(state.cpu().numpy(), want), (P, root, n, algo)
+        if algo != O.BINOMIAL and sched.n_steps > 0:
+            # the same broadcast in three pieces cut at random steps, each piece one
+            # launch of the one-launch executor's kernel
+            H.refill(state, w)
+            ref = [H.host_row(w, r, state.shape[1]) for r in range(P)]
+            a = rnd.randrange(sched.n_steps + 1)
+            b = rnd.randrange(a, sched.n_steps + 1)
+            for (first, last) in ((0, a), (a, b), (b, sched.n_steps)):
+                plan.run_chain_steps(first, last)
+                O.run_steps(ref, sched, first, last)
+                assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (P, root, n, algo, first, last)
         plan.destroy()
         comm.destroy()
 
