@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs (profiles/), scaled by what the same counters read for a plain
 # copy of known size.  Valid only for the configuration it was measured on.
 MEASURED_TRAFFIC = {
-    ("P513_n128M", "chains", 8192, 2): 70.32e9,   # ring_chain (slab 8 KiB): 1.49 GB read + 68.83 GB written
+    ("P513_n128M", "chains", 8192, 2): 70.46e9,   # ring_chain (slab 8 KiB): 1.63 GB read + 68.83 GB written
     ("P513_n128M", "steps", 16384, 2): 268.4e6,   # step_copy (tile 16 KiB), a full ring step: 134.2 + 134.2 MB
 }
 
