@@ -8,9 +8,12 @@ and reported beside it, with the bytes-moved ratio.  Throughput is
 2 * bytes_moved / time: every moved byte is read once and written once.
 
 Prints one JSON line.  Also reports
-  roofline      per-launch figure of the ring-step copy kernel, timed with HIP
-                events around each launch on the launch stream
+  roofline      per-launch figure of the dominant kernel (the one launch that
+                carries scatter and ring, or the ring-step copy kernel), timed
+                with HIP events on the launch stream
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+  plain_fill_of_the_rank_buffers
+                the same buffers written once by torch's fill, for scale
 """
 
 from __future__ import annotations
@@ -290,6 +293,22 @@ def main() -> int:
     for p in plans.values():
         p.destroy()
     comm.destroy()
+    # for scale: the same rank buffers written once, one after the other, by torch's fill
+    # (everything that had to be checked has been; the buffers are not used again)
+    fill_ms = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for b in bufs:
+            b.fill_(0)
+        e1.record()
+        torch.cuda.synchronize()
+        fill_ms.append(e0.elapsed_time(e1))
+    out["plain_fill_of_the_rank_buffers"] = {
+        "ms": round(min(fill_ms), 3),
+        "write_gbs": round(w.P * stride / (min(fill_ms) * 1e-3) / 1e9, 1),
+        "note": "P fill launches writing every rank buffer once; no broadcast, for scale only",
+    }
     del bufs
     torch.cuda.empty_cache()
     if not args.no_cpu:
