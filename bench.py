@@ -172,15 +172,23 @@ def main() -> int:
         for _ in range(args.warmup):
             V.bcast_run(plan)
         torch.cuda.synchronize()
+        # K launches between two synchronisations give the figure; an event between
+        # consecutive launches (on the launch stream) gives each launch's own time
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for k in range(args.steps):
+            marks[k].record()
             V.bcast_run(plan)
+        marks[args.steps].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         ms = dt / args.steps * 1e3
+        each = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
         say(f"{algo}: {ms:.3f} ms per broadcast")
         results[algo] = {
             "ms_per_bcast": round(ms, 4),
+            "ms_median": round(each[len(each) // 2], 4),
+            "ms_min": round(each[0], 4),
             "bytes_moved": int(info.bytes_moved),
             "hbm_gbs": round(2.0 * info.bytes_moved / (ms * 1e-3) / 1e9, 2),
             "bcast_bandwidth_MBps": round(w.n / (ms * 1e-3) / 2**20, 1),
