@@ -229,8 +229,8 @@ def main() -> int:
             alg_bytes = 2.0 * float(ring_bytes.sum()) / launches
             kernel = "step_copy (one launch per ring step, tuned)"
         achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
-        size_key = (args.slab_bytes or 8192) if args.ring_executor == "chains" else int(info.tile_bytes)
-        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, size_key, args.chain_wgs_per_cu or 2))
+        size_key = (args.slab_bytes or 16384) if args.ring_executor == "chains" else int(info.tile_bytes)
+        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, size_key, args.chain_wgs_per_cu or 1))
         if args.pad:
             traffic = None
         roof = {
@@ -283,7 +283,7 @@ def main() -> int:
                         "seeded uniform random bytes; step = one tuned broadcast "
                         "(table generation + scatter + ring, one graph launch)",
             "tile_bytes": int(info.tile_bytes),
-            "slab_bytes": args.slab_bytes or 8192,
+            "slab_bytes": args.slab_bytes or 16384,
             "ring_executor": args.ring_executor,
             "rank_stride_bytes": stride,
         },

@@ -331,10 +331,11 @@ int vbcast_set_tile_bytes(size_t tile_bytes);
 
 /*
  * Slab size of the one-launch executor (VBCAST_RING_CHAINS) for plans created
- * afterwards: a power of two between 4096 and 65536 bytes (default 8192).  The
+ * afterwards: a power of two between 4096 and 65536 bytes (default 16384).  The
  * launch uses a smaller slab (down to 1024 bytes) when chunks are shorter than
- * this, and down to 4096 bytes when the message has fewer slabs than there are
- * resident workgroups.  Process-wide; returns ARG for other values.
+ * this, or hold fewer than four slabs without being a whole number of them, and
+ * down to 4096 bytes when the message has fewer slabs than there are resident
+ * workgroups.  Process-wide; returns ARG for other values.
  */
 int vbcast_set_chain_slab_bytes(size_t slab_bytes);
 
@@ -358,7 +359,7 @@ int vbcast_set_chain_slab_bytes(size_t slab_bytes);
  */
 int vbcast_set_ring_executor(int mode);
 
-/* Resident workgroups per compute unit for VBCAST_RING_CHAINS (1..16, default 2);
+/* Resident workgroups per compute unit for VBCAST_RING_CHAINS (1..16, default 1);
  * together with the slab size this sets how many bytes are in flight at once. */
 int vbcast_set_chain_workgroups_per_cu(int k);
 

@@ -60,9 +60,9 @@ namespace {
 thread_local std::string g_hip_msg;
 thread_local std::string g_text;
 std::atomic<int> g_tile_log2{14};
-std::atomic<int> g_slab_log2{13};
+std::atomic<int> g_slab_log2{14};
 std::atomic<int> g_ring_executor{VBCAST_RING_CHAINS};
-std::atomic<int> g_chain_wgs_per_cu{2};
+std::atomic<int> g_chain_wgs_per_cu{1};
 
 int hip_fail(hipError_t e, const char *what) {
     g_hip_msg = std::string(what) + ": " + hipGetErrorString(e);

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 ALGOS = [O.NATIVE, O.TUNED]
 DEFAULT_TILE = 16384
-DEFAULT_SLAB = 8192
+DEFAULT_SLAB = 16384
 
 
 @pytest.fixture(scope="module")
@@ -493,9 +493,11 @@ def test_paper_sweep_shapes(V, P, n):
 @pytest.mark.parametrize("P", [5, 16, 33])
 def test_chunk_sizes_around_the_slab_sizes(V, P):
     """The one-launch executor picks its slab (1, 2, 4, 8 KiB) and its kernel from
-    the chunk size: chunk sizes one below, at and one above every switch, with a
+    the chunk size: chunk sizes one below, at and one above every switch
+    (and where a chunk holds one and four of the largest slab), with a
     last chunk P - 1 bytes short and with an exact fit."""
-    for ss in (1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8192, 8193):
+    for ss in (1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8192, 8193, 16383, 16384,
+               16385, 65535, 65536, 65537):
         for n in (P * ss, P * ss - (P - 1)):
             w = I.Workload(f"slab_P{P}_n{n}", P, P - 2, n, seed=99_000 + P + ss)
             assert -(-n // P) == ss
