@@ -34,8 +34,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs (profiles/), scaled by what the same counters read for a plain
 # copy of known size.  Valid only for the configuration it was measured on.
 MEASURED_TRAFFIC = {
-    ("P513_n128M", "chains", 8192, 2): 70.46e9,   # ring_chain (slab 8 KiB): 1.63 GB read + 68.83 GB written
-    ("P513_n128M", "steps", 16384, 2): 268.4e6,   # step_copy (tile 16 KiB), a full ring step: 134.2 + 134.2 MB
+    # ring_chain, slab 16 KiB, 1 workgroup per CU: 0.85 GB read + 68.83 GB written
+    ("P513_n128M", "chains", 16384, 1): 69.68e9,
+    # step_copy, tile 16 KiB, a full ring step: 134.2 + 134.2 MB
+    ("P513_n128M", "steps", 16384, None): 268.4e6,
 }
 
 
@@ -230,7 +232,8 @@ def main() -> int:
             kernel = "step_copy (one launch per ring step, tuned)"
         achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
         size_key = (args.slab_bytes or 16384) if args.ring_executor == "chains" else int(info.tile_bytes)
-        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, size_key, args.chain_wgs_per_cu or 1))
+        wgs_key = (args.chain_wgs_per_cu or 1) if args.ring_executor == "chains" else None
+        traffic = MEASURED_TRAFFIC.get((w.name, args.ring_executor, size_key, wgs_key))
         if args.pad:
             traffic = None
         roof = {
