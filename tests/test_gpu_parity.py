@@ -290,6 +290,25 @@ def test_other_tile_sizes(V, tile):
         V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
 
 
+@pytest.mark.parametrize("wgs", [2, 3, 5, 16])
+def test_other_numbers_of_chain_workgroups(V, wgs):
+    """The one-launch executor with other numbers of resident workgroups per
+    compute unit (the grid and the runs of slabs per XCD follow from it)."""
+    V.vbcast_set_chain_workgroups_per_cu(wgs)
+    try:
+        for name in ("P24_n4M", "P96_n12M_ragged"):
+            w = I.workload(name)
+            state, comm, plan = make(V, w, O.TUNED)
+            want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+            plan.run()
+            sync()
+            assert np.array_equal(state.cpu().numpy(), want), (name, wgs)
+            plan.destroy()
+            comm.destroy()
+    finally:
+        V.vbcast_set_chain_workgroups_per_cu(1)
+
+
 def test_timed_steps_report_a_time_per_step(V):
     w = I.workload("P24_n4M")
     state, comm, plan = make(V, w, O.TUNED)
