@@ -106,3 +106,23 @@ def test_error_texts():
     with pytest.raises(V.VbcastError) as e:
         V.Comm([0x1008], 16)
     assert e.value.code == V.ERR_ALIGN
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and as C++), with
+    nothing but standard headers behind it."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler here")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "vbcast.h"\n'
+                   "int main(void) { vbcast_plan_info i; vbcast_census c; (void)i; (void)c; "
+                   "return VBCAST_SUCCESS; }\n")
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only"],
+                ["g++", "-std=c++11", "-x", "c++", "-Wall", "-Wextra", "-Werror", "-fsyntax-only"]):
+        if shutil.which(cmd[0]) is None:
+            continue
+        r = subprocess.run(cmd + ["-I", inc, str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
