@@ -16,7 +16,7 @@ def shapes(draw):
     return P, root, n
 
 
-@settings(max_examples=120, deadline=None)
+@settings(max_examples=120, deadline=None, derandomize=True, database=None)
 @given(shapes(), st.sampled_from([O.NATIVE, O.TUNED, O.BINOMIAL, O.SCATTER_RDB]))
 def test_any_schedule_is_a_broadcast(shape, algo):
     P, root, n = shape
@@ -35,7 +35,7 @@ def test_any_schedule_is_a_broadcast(shape, algo):
             assert 0 <= s < P and 0 <= d < P and s != d and ln > 0 and off + ln <= n
 
 
-@settings(max_examples=120, deadline=None)
+@settings(max_examples=120, deadline=None, derandomize=True, database=None)
 @given(shapes())
 def test_byte_and_message_counts(shape):
     P, root, n = shape
