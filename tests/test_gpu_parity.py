@@ -309,6 +309,36 @@ def test_other_numbers_of_chain_workgroups(V, wgs):
         V.vbcast_set_chain_workgroups_per_cu(1)
 
 
+def test_plans_give_their_device_memory_back(V):
+    """Two hundred plans (and a three-phase plan each tenth time) created, run and
+    destroyed: the device's free memory ends where it started."""
+    import torch
+    w = I.workload("P24_n4M")
+    state = H.device_buffers(w)
+    comm = V.Comm([state[r].data_ptr() for r in range(w.P)], state.shape[1])
+    # the runtime sets up a pool of its own on the first plan: not ours, not counted
+    for warm in (V.bcast_plan(comm, w.n, 1, w.root, V.TUNED), V.bcast_plan_smp(comm, w.n, 1, w.root, 5, "tuned")):
+        warm.run()
+        sync()
+        warm.destroy()
+    sync()
+    free0 = torch.cuda.mem_get_info()[0]
+    for k in range(200):
+        plan = V.bcast_plan(comm, w.n, 1, w.root, ALGOS[k % 2])
+        plan.run()
+        if k % 10 == 0:
+            smp = V.bcast_plan_smp(comm, w.n, 1, w.root, 5, "tuned")
+            smp.run()
+            sync()
+            smp.destroy()
+        sync()
+        plan.destroy()
+    sync()
+    free1 = torch.cuda.mem_get_info()[0]
+    assert free0 - free1 < (4 << 20), (free0, free1)
+    comm.destroy()
+
+
 def test_timed_steps_report_a_time_per_step(V):
     w = I.workload("P24_n4M")
     state, comm, plan = make(V, w, O.TUNED)
