@@ -126,3 +126,14 @@ def test_header_is_plain_c(tmp_path):
             continue
         r = subprocess.run(cmd + ["-I", inc, str(src)], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_bench_runs_on_one_gpu_only():
+    """bench.py --gpus N with N above 1 exits with a message that says so, before
+    anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
