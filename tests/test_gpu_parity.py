@@ -348,7 +348,9 @@ def test_timed_steps_report_a_time_per_step(V):
     assert np.array_equal(state.cpu().numpy(), want)
     H.refill(state, w)
     phases = plan.run_timed()
-    assert phases.shape == (3,) and (phases > 0).all()
+    # with the one-launch executor the scatter phase launches nothing: its slot is
+    # the gap between two event records, which may read as zero
+    assert phases.shape == (3,) and phases[0] > 0 and phases[1] >= 0 and phases[2] > 0
     assert np.array_equal(state.cpu().numpy(), want)
     plan.destroy()
     comm.destroy()
