@@ -85,7 +85,8 @@ enum {
     VBCAST_ERR_COUNT = 3, /* count * dtype_size overflows or exceeds the rank buffers */
     VBCAST_ERR_ALIGN = 4, /* a rank buffer is not 16-byte aligned */
     VBCAST_ERR_HIP = 5,   /* a HIP runtime call failed */
-    VBCAST_ERR_NOMEM = 6  /* host or device allocation failed */
+    VBCAST_ERR_NOMEM = 6, /* host or device allocation failed */
+    VBCAST_ERR_LIMIT = 7  /* more ranks than the static tables of bcast_run_static hold */
 };
 
 /* Largest communicator accepted (tables grow with P * P). */
@@ -139,6 +140,39 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
  * Errors: ARG (null), HIP.
  */
 int bcast_run(const vbcast_plan *plan, void *hip_stream);
+
+/* Largest communicator bcast_run_static accepts. */
+#define VBCAST_STATIC_MAX_RANKS 513
+
+/*
+ * One whole broadcast without any allocation: for callers that cannot allocate
+ * device memory at the point of the call (code under stream capture into a graph,
+ * tight serving loops, harnesses that forbid allocation).  It does what
+ * bcast_plan followed by bcast_run does with the one-launch executor
+ * (VBCAST_RING_CHAINS) - table generation on the device, then scatter and ring
+ * in one launch - but keeps the tables in a fixed 10 MiB array that is part of
+ * the library's device code (every GPU the library runs on holds its own copy
+ * until the process ends) instead of a per-plan allocation, and creates no plan
+ * object, graph, stream or event.  The call makes no hipMalloc, hipFree or other
+ * allocating call; it enqueues three kernels on hip_stream and returns without
+ * waiting.  Afterwards the rank buffers hold what bcast_run leaves.
+ *   comm        communicator (created beforehand; vbcast_comm_create is the set-up
+ *               step that allocates and that looks up the table array's address on
+ *               the device); its device must be current.  At most
+ *               VBCAST_STATIC_MAX_RANKS ranks.
+ *   count, dtype_size, root   as in bcast_plan; any message size the rank buffers
+ *               hold (the tables grow with the number of ranks only).
+ *   algo        VBCAST_NATIVE or VBCAST_TUNED.
+ * All calls on one GPU share the one table array, which keeps the previous call's
+ * contents (every entry a call reads it has written itself first): calls on the
+ * same stream are ordered and safe; calls that overlap in time on one GPU (other
+ * streams, other threads) race.  The chain-slab and workgroups-per-CU settings
+ * apply as they do to plans.
+ * Errors: ARG (null, other algo, other device current), LIMIT (more than
+ * VBCAST_STATIC_MAX_RANKS ranks), ROOT, COUNT, HIP.
+ */
+int bcast_run_static(const vbcast_comm *comm, size_t count, size_t dtype_size, int root, int algo,
+                     void *hip_stream);
 
 /*
  * Run steps [first, last) only, as plain kernel launches on hip_stream (no

@@ -8,8 +8,10 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <unordered_map>
 #include <vector>
 
@@ -21,6 +23,7 @@ struct vbcast_comm {
     int P = 0;
     size_t buf_bytes = 0;
     int device = 0;
+    int compute_units = 256;  // of `device`, read once at creation
     std::vector<void *> host_bases;
     uint8_t **dev_bases = nullptr;
 };
@@ -90,6 +93,93 @@ struct ArenaLayout {
         return at;
     }
 };
+
+// Places every plan array of `pa` (P, L, n_steps, algo and tile_cap already set)
+// one after the other from `base`, each on a 256-byte boundary, and returns the
+// bytes they take together; with base == nullptr it only measures.  Without
+// `tile_maps` the tile maps and the census sums (needed by the per-step executor
+// and bcast_plan_census only) get no room and stay null.
+size_t bind_plan_arrays(PlanArrays &pa, char *base, bool tile_maps) {
+    const size_t S = (size_t)pa.n_steps, Pz = (size_t)pa.P;
+    const bool ring_algo = pa.algo == VBCAST_NATIVE || pa.algo == VBCAST_TUNED;
+    ArenaLayout lay;
+    auto place = [&](auto *&field, size_t bytes) {
+        const size_t at = lay.take(bytes);
+        using T = std::remove_reference_t<decltype(field)>;
+        field = (base && bytes) ? reinterpret_cast<T>(base + at) : nullptr;
+    };
+    place(pa.chunk_off, sizeof(uint64_t) * (Pz + 1));
+    place(pa.chunk_len, sizeof(uint64_t) * Pz);
+    place(pa.rel, sizeof(int32_t) * Pz);
+    place(pa.left, sizeof(int32_t) * Pz);
+    place(pa.right, sizeof(int32_t) * Pz);
+    place(pa.sw_step, sizeof(int32_t) * Pz);
+    place(pa.sw_flag, sizeof(int32_t) * Pz);
+    place(pa.rows, sizeof(Row) * S * Pz);
+    place(pa.chain, ring_algo ? sizeof(uint64_t) * Pz * ((size_t)pa.L + Pz - 1) : 0);
+    place(pa.tile_ptr, sizeof(uint32_t) * S * (Pz + 1));
+    place(pa.tiles, tile_maps ? sizeof(Tile) * S * (size_t)pa.tile_cap : 0);
+    place(pa.step_rows, sizeof(uint32_t) * S);
+    place(pa.step_tiles, sizeof(uint32_t) * S);
+    place(pa.step_posted, sizeof(uint32_t) * S);
+    place(pa.step_mismatch, sizeof(uint32_t) * S);
+    place(pa.step_bytes, sizeof(uint64_t) * S);
+    place(pa.census, tile_maps ? sizeof(uint64_t) * 4 * S : 0);
+    return lay.total;
+}
+
+// ---------------------------------------------------------------------------
+// bcast_run_static: the tables of one broadcast in memory that exists without any
+// allocation - a file-scope device array, present on every GPU the library runs
+// on from the moment its code is loaded until the process ends.
+//
+// In host code the array's name stands for the symbol, not for a device address:
+// the address on a given GPU comes from hipGetSymbolAddress, asked once per
+// device with that device current (every GPU has its own copy at its own
+// address), and only that pointer is ever handed to a kernel.
+// ---------------------------------------------------------------------------
+constexpr size_t kScratchBytes = size_t(10) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// The address of `scratch` on `device`, which must be the current device.
+int scratch_on_device(int device, void **out) {
+    if (device < 0 || device >= kMaxDevices) return VBCAST_ERR_ARG;
+    std::lock_guard<std::mutex> hold(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p) {
+            g_hip_msg = "hipGetSymbolAddress(scratch) gave no address";
+            return VBCAST_ERR_HIP;
+        }
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return VBCAST_SUCCESS;
+}
+
+void describe_plan(PlanArrays &pa, int P, int root, int algo, uint64_t n, int tile_log2,
+                   uint32_t tile_cap) {
+    pa.P = P;
+    pa.root = root;
+    pa.algo = algo;
+    pa.L = ceil_log2_int(P);
+    pa.n_scatter = algo == VBCAST_BINOMIAL ? 0 : pa.L;
+    pa.n_steps = P <= 1 ? 0
+                 : algo == VBCAST_BINOMIAL ? pa.L
+                 : algo == VBCAST_SCATTER_RDB ? 2 * pa.L
+                                              : pa.L + P - 1;
+    pa.tile_log2 = tile_log2;
+    pa.slab_log2 = g_slab_log2.load();
+    pa.tile_cap = tile_cap;
+    pa.n = n;
+    pa.ss = (n + (uint64_t)P - 1) / (uint64_t)P;
+}
 
 int launch_steps(const vbcast_plan *plan, int first, int last, hipStream_t stream,
                  hipEvent_t *marks) {
@@ -223,6 +313,24 @@ int vbcast_comm_create(int P, void *const *rank_bufs, size_t buf_bytes, vbcast_c
     c->buf_bytes = buf_bytes;
     c->host_bases.assign(rank_bufs, rank_bufs + P);
     hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess &&
+            cus > 0)
+            c->compute_units = cus;
+        else
+            (void)hipGetLastError();
+    }
+    if (e == hipSuccess) {
+        // set-up is also where the address of the static table memory on this device
+        // is asked for, so that bcast_run_static itself only looks it up
+        void *unused = nullptr;
+        const int rc = scratch_on_device(c->device, &unused);
+        if (rc != VBCAST_SUCCESS) {
+            delete c;
+            return rc;
+        }
+    }
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&c->dev_bases), sizeof(void *) * P);
     if (e == hipSuccess)
         e = hipMemcpy(c->dev_bases, c->host_bases.data(), sizeof(void *) * P, hipMemcpyHostToDevice);
@@ -277,43 +385,12 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     if (!plan) return VBCAST_ERR_NOMEM;
     plan->comm = comm;
     PlanArrays &pa = plan->pa;
-    pa.P = P;
-    pa.root = root;
-    pa.algo = algo;
-    pa.L = ceil_log2_int(P);
-    pa.n_scatter = algo == VBCAST_BINOMIAL ? 0 : pa.L;
-    pa.n_steps = P <= 1 ? 0
-                 : algo == VBCAST_BINOMIAL ? pa.L
-                 : algo == VBCAST_SCATTER_RDB ? 2 * pa.L
-                                              : pa.L + P - 1;
-    pa.tile_log2 = tile_log2;
-    pa.slab_log2 = g_slab_log2.load();
-    pa.tile_cap = (uint32_t)tile_cap64;
-    pa.n = n;
-    pa.ss = (n + (uint64_t)P - 1) / (uint64_t)P;
+    describe_plan(pa, P, root, algo, n, tile_log2, (uint32_t)tile_cap64);
 
-    const size_t S = (size_t)pa.n_steps, Pz = (size_t)P;
-    ArenaLayout lay;
-    const size_t o_chunk_off = lay.take(sizeof(uint64_t) * (Pz + 1));
-    const size_t o_chunk_len = lay.take(sizeof(uint64_t) * Pz);
-    const size_t o_rel = lay.take(sizeof(int32_t) * Pz);
-    const size_t o_left = lay.take(sizeof(int32_t) * Pz);
-    const size_t o_right = lay.take(sizeof(int32_t) * Pz);
-    const size_t o_sw_step = lay.take(sizeof(int32_t) * Pz);
-    const size_t o_sw_flag = lay.take(sizeof(int32_t) * Pz);
-    const size_t o_rows = lay.take(sizeof(Row) * S * Pz);
-    const size_t o_chain =
-        lay.take(ring_algo ? sizeof(uint64_t) * Pz * ((size_t)ceil_log2_int(P) + Pz - 1) : 0);
-    const size_t o_tile_ptr = lay.take(sizeof(uint32_t) * S * (Pz + 1));
-    const size_t o_tiles = lay.take(sizeof(Tile) * S * (size_t)pa.tile_cap);
-    const size_t o_step_rows = lay.take(sizeof(uint32_t) * S);
-    const size_t o_step_tiles = lay.take(sizeof(uint32_t) * S);
-    const size_t o_step_posted = lay.take(sizeof(uint32_t) * S);
-    const size_t o_step_mismatch = lay.take(sizeof(uint32_t) * S);
-    const size_t o_step_bytes = lay.take(sizeof(uint64_t) * S);
-    const size_t o_census = lay.take(sizeof(uint64_t) * 4 * S);
+    const size_t S = (size_t)pa.n_steps;
+    const size_t arena_bytes = bind_plan_arrays(pa, nullptr, /*tile_maps=*/true);
 
-    hipError_t e = hipMalloc(&plan->arena, lay.total);
+    hipError_t e = hipMalloc(&plan->arena, arena_bytes);
     if (e != hipSuccess) {
         delete plan;
         if (e == hipErrorOutOfMemory) {
@@ -322,32 +399,10 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
         }
         return hip_fail(e, "hipMalloc(plan)");
     }
-    char *base = static_cast<char *>(plan->arena);
-    pa.chunk_off = reinterpret_cast<uint64_t *>(base + o_chunk_off);
-    pa.chunk_len = reinterpret_cast<uint64_t *>(base + o_chunk_len);
-    pa.rel = reinterpret_cast<int32_t *>(base + o_rel);
-    pa.left = reinterpret_cast<int32_t *>(base + o_left);
-    pa.right = reinterpret_cast<int32_t *>(base + o_right);
-    pa.sw_step = reinterpret_cast<int32_t *>(base + o_sw_step);
-    pa.sw_flag = reinterpret_cast<int32_t *>(base + o_sw_flag);
-    pa.rows = reinterpret_cast<Row *>(base + o_rows);
-    pa.chain = reinterpret_cast<uint64_t *>(base + o_chain);
+    (void)bind_plan_arrays(pa, static_cast<char *>(plan->arena), /*tile_maps=*/true);
     pa.bases = comm->dev_bases;
     plan->ring_executor = g_ring_executor.load();
-    {
-        int cus = 0;
-        hipError_t ce = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, comm->device);
-        if (ce != hipSuccess || cus < 1) cus = 256;
-        plan->chain_grid = (uint32_t)cus * (uint32_t)g_chain_wgs_per_cu.load();
-    }
-    pa.tile_ptr = reinterpret_cast<uint32_t *>(base + o_tile_ptr);
-    pa.tiles = reinterpret_cast<Tile *>(base + o_tiles);
-    pa.step_rows = reinterpret_cast<uint32_t *>(base + o_step_rows);
-    pa.step_tiles = reinterpret_cast<uint32_t *>(base + o_step_tiles);
-    pa.step_posted = reinterpret_cast<uint32_t *>(base + o_step_posted);
-    pa.step_mismatch = reinterpret_cast<uint32_t *>(base + o_step_mismatch);
-    pa.step_bytes = reinterpret_cast<uint64_t *>(base + o_step_bytes);
-    pa.census = reinterpret_cast<uint64_t *>(base + o_census);
+    plan->chain_grid = (uint32_t)comm->compute_units * (uint32_t)g_chain_wgs_per_cu.load();
 
     int rc = VBCAST_SUCCESS;
     e = vbcast::launch_plan_kernels(pa, pa.n_steps, stream);
@@ -391,6 +446,42 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
 int bcast_run(const vbcast_plan *plan, void *hip_stream) {
     if (!plan || !plan->exec) return VBCAST_ERR_ARG;
     HIP_TRY(hipGraphLaunch(plan->exec, static_cast<hipStream_t>(hip_stream)));
+    return VBCAST_SUCCESS;
+}
+
+int bcast_run_static(const vbcast_comm *comm, size_t count, size_t dtype_size, int root, int algo,
+                     void *hip_stream) {
+    if (!comm) return VBCAST_ERR_ARG;
+    if (algo != VBCAST_NATIVE && algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
+    const int P = comm->P;
+    if (P > VBCAST_STATIC_MAX_RANKS) return VBCAST_ERR_LIMIT;
+    if (root < 0 || root >= P) return VBCAST_ERR_ROOT;
+    if (dtype_size != 0 && count > SIZE_MAX / dtype_size) return VBCAST_ERR_COUNT;
+    const uint64_t n = (uint64_t)count * (uint64_t)dtype_size;
+    if (n > comm->buf_bytes) return VBCAST_ERR_COUNT;
+    int dev = -1;
+    hipError_t de = hipGetDevice(&dev);
+    if (de != hipSuccess) return hip_fail(de, "hipGetDevice");
+    if (dev != comm->device) return VBCAST_ERR_ARG;
+
+    PlanArrays pa{};
+    describe_plan(pa, P, root, algo, n, g_tile_log2.load(), 0);
+    if (bind_plan_arrays(pa, nullptr, /*tile_maps=*/false) > kScratchBytes) return VBCAST_ERR_LIMIT;
+    void *tables = nullptr;
+    const int rc = scratch_on_device(dev, &tables);   // looked up at vbcast_comm_create
+    if (rc != VBCAST_SUCCESS) return rc;
+    (void)bind_plan_arrays(pa, static_cast<char *>(tables), /*tile_maps=*/false);
+    pa.bases = comm->dev_bases;
+
+    // Every table entry the copy kernel reads is written by the table kernels of
+    // this same call first, so nothing of an earlier call's tables has to be cleared.
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = vbcast::launch_plan_kernels(pa, 0, stream);
+    if (e != hipSuccess) return hip_fail(e, "plan kernels");
+    if (pa.n_steps == 0) return VBCAST_SUCCESS;
+    const uint32_t grid = (uint32_t)comm->compute_units * (uint32_t)g_chain_wgs_per_cu.load();
+    e = vbcast::launch_ring_chain(pa, grid, 0, pa.n_steps, stream);
+    if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
     return VBCAST_SUCCESS;
 }
 
@@ -778,6 +869,8 @@ const char *bcast_strerror(int code) {
         case VBCAST_ERR_COUNT: return "message size overflows or exceeds the rank buffers";
         case VBCAST_ERR_ALIGN: return "rank buffer is not 16-byte aligned";
         case VBCAST_ERR_NOMEM: return "out of memory";
+        case VBCAST_ERR_LIMIT:
+            return "communicator too large for the static tables of bcast_run_static";
         case VBCAST_ERR_HIP:
             g_text = "HIP runtime failure: " + g_hip_msg;
             return g_text.c_str();

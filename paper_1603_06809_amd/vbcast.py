@@ -28,10 +28,11 @@ ALGO_NAMES = {v: k for k, v in ALGOS.items()}
 RING_STEPS = 0
 RING_CHAINS = 1
 
-SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM = range(7)
+SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM, ERR_LIMIT = range(8)
+STATIC_MAX_RANKS = 513
 
 EXPORTS = [
-    "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_steps", "bcast_run_chain_steps",
+    "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_static", "bcast_run_steps", "bcast_run_chain_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
     "bcast_plan_export_tiles", "bcast_plan_export_chain", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
     "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
@@ -89,6 +90,7 @@ def lib():
     L.vbcast_comm_destroy.argtypes = [vp]
     L.bcast_plan.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, vp, C.POINTER(vp)]
     L.bcast_run.argtypes = [vp, vp]
+    L.bcast_run_static.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, vp]
     L.bcast_run_steps.argtypes = [vp, C.c_int, C.c_int, vp]
     L.bcast_run_chain_steps.argtypes = [vp, C.c_int, C.c_int, vp]
     L.bcast_run_steps_timed.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_float)]
@@ -338,6 +340,13 @@ def bcast_plan(comm: Comm, count: int, dtype_size: int, root: int, algo, stream=
 
 def bcast_run(plan: Plan, stream=None) -> None:
     plan.run(stream)
+
+
+def bcast_run_static(comm: Comm, count: int, dtype_size: int, root: int, algo, stream=None) -> None:
+    """One whole broadcast with the tables in the library's static device array
+    (no allocation); see bcast_run_static in include/vbcast.h."""
+    _check(lib().bcast_run_static(comm._h, count, dtype_size, root, ALGOS.get(algo, algo),
+                                  _stream_handle(stream)))
 
 
 def bcast_run_steps(plan: Plan, first: int, last: int, stream=None) -> None:
