@@ -177,7 +177,11 @@ int bcast_run_static(const vbcast_comm *comm, size_t count, size_t dtype_size, i
 /*
  * Run steps [first, last) only, as plain kernel launches on hip_stream (no
  * graph, tables as they are in device memory), asynchronously.  Used to look at
- * the state between steps.  Steps count scatter levels first, then ring steps.
+ * the state between steps.  Steps count scatter levels first [Sec. III-A: one
+ * level of the binomial tree], then ring steps [Sec. IV, listing: one iteration
+ * i of the loop over comm_size - 1 exchanges, i.e. one send to the right
+ * neighbour and one receive from the left per rank, or only one of the two for a
+ * rank past its switch point].
  * Errors: ARG (null, first < 0, first > last, last > n_steps), HIP.
  */
 int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stream);
@@ -241,7 +245,12 @@ int bcast_plan_info(const vbcast_plan *plan, vbcast_plan_info *info);
 
 /*
  * Copy the step tables to the host (synchronous copies; the caller makes sure no
- * launch of this plan is still running).  Any output may be NULL.
+ * launch of this plan is still running).  Any output may be NULL.  A row is one
+ * message of the schedule: for a ring step the sender, its right neighbour, and
+ * the displacement and count the sender computes for that iteration [Sec. IV,
+ * listing: right_disp / right_count, equal to the receiver's left_disp /
+ * left_count]; for a scatter level the subtree root, the rank it hands the upper
+ * half of its chunks to, and that range as one extent [Sec. III-A].
  *   step_ptr    n_steps + 1 entries; rows of step s are [step_ptr[s], step_ptr[s+1])
  *   src, dst    one entry per row: absolute ranks
  *   off, len    one entry per row: byte offset and length
@@ -396,6 +405,18 @@ int vbcast_set_ring_executor(int mode);
 /* Resident workgroups per compute unit for VBCAST_RING_CHAINS (1..16, default 1);
  * together with the slab size this sets how many bytes are in flight at once. */
 int vbcast_set_chain_workgroups_per_cu(int k);
+
+/*
+ * Number of accelerator dies (XCDs) the copy kernels assume when they map
+ * workgroups to pieces of the message, for communicators created afterwards:
+ * the hardware deals workgroup b to die b mod n_xcd, and the kernels give every
+ * die a contiguous share of the work so that its addresses spread over all
+ * channels of its own L2.  0 (default) = ask the device (8 on the unpartitioned
+ * part; 8 is also assumed when the device does not say).  Any value gives the
+ * same results - the mapping is a permutation of the pieces - only the speed
+ * differs.  1..64 or 0; ARG otherwise.  Process-wide.
+ */
+int vbcast_set_xcd_count(int n_xcd);
 
 /* Text for an error code; never NULL.  The pointer is valid until the calling
  * thread's next library call. */

@@ -85,16 +85,17 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                                                        uint8_t *const *__restrict__ bases, int P,
                                                        int L, int root, uint64_t n, uint64_t ss,
                                                        uint32_t n_slabs, uint32_t xcd_run,
-                                                       uint32_t first_step, uint32_t last_step) {
+                                                       uint32_t n_xcd, uint32_t first_step,
+                                                       uint32_t last_step) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
-    // Workgroups are handed to the XCDs round-robin (workgroup id mod 8).  Give
-    // each XCD runs of `xcd_run` consecutive slabs (64 KiB) instead of every
-    // eighth slab, so that the addresses one XCD touches spread over all of its L2
-    // channels, while the eight XCDs together still sweep one contiguous window.
-    const uint32_t W = gridDim.x;  // a multiple of 8; W / 8 is a multiple of xcd_run
-    const uint32_t in_xcd = blockIdx.x >> 3;
-    const uint32_t first = (in_xcd / xcd_run) * 8u * xcd_run + (blockIdx.x & 7u) * xcd_run +
+    // Workgroups are handed to the XCDs round-robin (workgroup id mod n_xcd).
+    // Give each XCD runs of `xcd_run` consecutive slabs (64 KiB) instead of every
+    // n-th slab, so that the addresses one XCD touches spread over all of its L2
+    // channels, while the XCDs together still sweep one contiguous window.
+    const uint32_t W = gridDim.x;  // a multiple of n_xcd; W / n_xcd is a multiple of xcd_run
+    const uint32_t in_xcd = blockIdx.x / n_xcd;
+    const uint32_t first = (in_xcd / xcd_run) * n_xcd * xcd_run + (blockIdx.x % n_xcd) * xcd_run +
                            (in_xcd % xcd_run);
     for (uint32_t slab = first; slab < n_slabs; slab += W) {
         const uint64_t lo = (uint64_t)slab << TILE_LOG2;
@@ -286,15 +287,16 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, in
     if (n_slabs64 > 0xffffffffull) return hipErrorInvalidValue;
     const uint32_t n_slabs = (uint32_t)n_slabs64;
     uint32_t grid = grid64 > n_slabs ? n_slabs : (uint32_t)grid64;
-    grid = (grid + 7u) & ~7u;  // whole rounds over the 8 XCDs
+    const uint32_t n_xcd = pa.n_xcd > 0 ? (uint32_t)pa.n_xcd : 1u;
+    grid = (grid + n_xcd - 1u) / n_xcd * n_xcd;  // whole rounds over the XCDs
     // slabs per XCD run: 64 KiB worth, but a divisor of the workgroups per XCD
     uint32_t xcd_run = tl < 16 ? (1u << (16 - tl)) : 1u;
-    while ((grid >> 3) % xcd_run != 0) xcd_run >>= 1;
+    while ((grid / n_xcd) % xcd_run != 0) xcd_run >>= 1;
     const dim3 g(grid);
     // one 16-byte word per lane in the two smallest slabs, so fewer lanes there
 #define VB_LAUNCH(TL, LANES)                                                                 \
     hipLaunchKernelGGL((ring_chain<TL, LANES>), g, dim3(LANES), 0, stream, pa.chain,         \
-                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs, xcd_run, s0, s1)
+                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs, xcd_run, n_xcd, s0, s1)
     switch (tl) {
         case 10: VB_LAUNCH(10, 64); break;
         case 11: VB_LAUNCH(11, 128); break;

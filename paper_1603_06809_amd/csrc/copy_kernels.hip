@@ -27,17 +27,17 @@ template <int TILE_LOG2>
 __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ rows,
                                                       const Tile *__restrict__ tiles,
                                                       uint8_t *const *__restrict__ bases,
-                                                      uint32_t n_tiles) {
+                                                      uint32_t n_tiles, uint32_t n_xcd) {
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     constexpr int WORDS = (int)(TILE / 16);      // 16-byte words in a full tile
     constexpr int PER_LANE = WORDS / kThreads;   // words per lane in a full tile
     static_assert(PER_LANE >= 1, "tile too small for the workgroup");
 
-    // Workgroups go to the XCDs round-robin (workgroup id mod 8): give each XCD a
-    // contiguous eighth of the step's tiles rather than every eighth tile, so
-    // that its addresses spread over all of its L2 channels.
-    const uint32_t per_xcd = gridDim.x >> 3;  // the grid is a multiple of 8
-    const uint32_t tile_id = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    // Workgroups go to the XCDs round-robin (workgroup id mod the number of
+    // XCDs): give each XCD a contiguous share of the step's tiles rather than
+    // every n-th tile, so that its addresses spread over all of its L2 channels.
+    const uint32_t per_xcd = gridDim.x / n_xcd;  // the grid is a multiple of n_xcd
+    const uint32_t tile_id = (blockIdx.x % n_xcd) * per_xcd + (blockIdx.x / n_xcd);
     if (tile_id >= n_tiles) return;
     const Tile t = tiles[tile_id];
     const Row r = rows[t.row];
@@ -93,14 +93,15 @@ __global__ __launch_bounds__(kThreads) void step_copy(const Row *__restrict__ ro
 }  // namespace
 
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
-                            uint32_t n_tiles, int tile_log2, hipStream_t stream) {
-    const dim3 grid((n_tiles + 7u) & ~7u), block(kThreads);
+                            uint32_t n_tiles, int tile_log2, int n_xcd, hipStream_t stream) {
+    const uint32_t x = n_xcd > 0 ? (uint32_t)n_xcd : 1u;
+    const dim3 grid((n_tiles + x - 1u) / x * x), block(kThreads);
     switch (tile_log2) {
-        case 12: hipLaunchKernelGGL(step_copy<12>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
-        case 13: hipLaunchKernelGGL(step_copy<13>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
-        case 14: hipLaunchKernelGGL(step_copy<14>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
-        case 15: hipLaunchKernelGGL(step_copy<15>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
-        case 16: hipLaunchKernelGGL(step_copy<16>, grid, block, 0, stream, rows, tiles, bases, n_tiles); break;
+        case 12: hipLaunchKernelGGL(step_copy<12>, grid, block, 0, stream, rows, tiles, bases, n_tiles, x); break;
+        case 13: hipLaunchKernelGGL(step_copy<13>, grid, block, 0, stream, rows, tiles, bases, n_tiles, x); break;
+        case 14: hipLaunchKernelGGL(step_copy<14>, grid, block, 0, stream, rows, tiles, bases, n_tiles, x); break;
+        case 15: hipLaunchKernelGGL(step_copy<15>, grid, block, 0, stream, rows, tiles, bases, n_tiles, x); break;
+        case 16: hipLaunchKernelGGL(step_copy<16>, grid, block, 0, stream, rows, tiles, bases, n_tiles, x); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -24,6 +24,7 @@ struct vbcast_comm {
     size_t buf_bytes = 0;
     int device = 0;
     int compute_units = 256;  // of `device`, read once at creation
+    int n_xcd = 8;            // accelerator dies of `device` (workgroups are dealt to them round-robin)
     std::vector<void *> host_bases;
     uint8_t **dev_bases = nullptr;
 };
@@ -66,6 +67,7 @@ std::atomic<int> g_tile_log2{14};
 std::atomic<int> g_slab_log2{14};
 std::atomic<int> g_ring_executor{VBCAST_RING_CHAINS};
 std::atomic<int> g_chain_wgs_per_cu{1};
+std::atomic<int> g_xcd_override{0};  // 0 = ask the device
 
 int hip_fail(hipError_t e, const char *what) {
     g_hip_msg = std::string(what) + ": " + hipGetErrorString(e);
@@ -190,7 +192,7 @@ int launch_steps(const vbcast_plan *plan, int first, int last, hipStream_t strea
         if (nt == 0) continue;
         HIP_TRY(vbcast::launch_step_copy(pa.rows + (size_t)s * pa.P,
                                          pa.tiles + (size_t)s * pa.tile_cap,
-                                         plan->comm->dev_bases, nt, pa.tile_log2, stream));
+                                         plan->comm->dev_bases, nt, pa.tile_log2, pa.n_xcd, stream));
     }
     if (marks) HIP_TRY(hipEventRecord(marks[last - first], stream));
     return VBCAST_SUCCESS;
@@ -299,6 +301,12 @@ int vbcast_set_chain_workgroups_per_cu(int k) {
     return VBCAST_SUCCESS;
 }
 
+int vbcast_set_xcd_count(int n_xcd) {
+    if (n_xcd < 0 || n_xcd > 64) return VBCAST_ERR_ARG;
+    g_xcd_override.store(n_xcd);
+    return VBCAST_SUCCESS;
+}
+
 int vbcast_comm_create(int P, void *const *rank_bufs, size_t buf_bytes, vbcast_comm **out) {
     if (!out) return VBCAST_ERR_ARG;
     *out = nullptr;
@@ -320,6 +328,14 @@ int vbcast_comm_create(int P, void *const *rank_bufs, size_t buf_bytes, vbcast_c
             c->compute_units = cus;
         else
             (void)hipGetLastError();
+        int xcds = 0;
+        if (g_xcd_override.load() > 0)
+            c->n_xcd = g_xcd_override.load();
+        else if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, c->device) == hipSuccess &&
+                 xcds > 0 && c->compute_units % xcds == 0)
+            c->n_xcd = xcds;
+        else
+            (void)hipGetLastError();   // not reported: keep 8, the full part's count
     }
     if (e == hipSuccess) {
         // set-up is also where the address of the static table memory on this device
@@ -386,6 +402,7 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     plan->comm = comm;
     PlanArrays &pa = plan->pa;
     describe_plan(pa, P, root, algo, n, tile_log2, (uint32_t)tile_cap64);
+    pa.n_xcd = comm->n_xcd;
 
     const size_t S = (size_t)pa.n_steps;
     const size_t arena_bytes = bind_plan_arrays(pa, nullptr, /*tile_maps=*/true);
@@ -466,6 +483,7 @@ int bcast_run_static(const vbcast_comm *comm, size_t count, size_t dtype_size, i
 
     PlanArrays pa{};
     describe_plan(pa, P, root, algo, n, g_tile_log2.load(), 0);
+    pa.n_xcd = comm->n_xcd;
     if (bind_plan_arrays(pa, nullptr, /*tile_maps=*/false) > kScratchBytes) return VBCAST_ERR_LIMIT;
     void *tables = nullptr;
     const int rc = scratch_on_device(dev, &tables);   // looked up at vbcast_comm_create

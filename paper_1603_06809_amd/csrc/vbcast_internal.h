@@ -37,6 +37,7 @@ struct PlanArrays {
     int32_t n_steps;    // all steps (0 when P == 1)
     int32_t tile_log2;  // copy tile of the per-step executor (tile maps)
     int32_t slab_log2;  // slab of the one-launch executor
+    int32_t n_xcd;      // accelerator dies (XCDs) of the device; workgroup b runs on XCD b mod n_xcd
     uint32_t tile_cap;  // tile slots per step
     uint64_t n, ss;
 
@@ -88,9 +89,10 @@ hipError_t launch_plan_kernels(const PlanArrays &pa, int tile_map_steps, hipStre
 // node when ranks sit on nodes in blocks of `ranks_per_node`; fills pa.census.
 hipError_t launch_plan_census(const PlanArrays &pa, int ranks_per_node, hipStream_t stream);
 
-// Enqueue the copy kernel of one step; `n_tiles` > 0 workgroups.
+// Enqueue the copy kernel of one step; `n_tiles` > 0 workgroups, dealt to the
+// device's `n_xcd` accelerator dies so that each takes a contiguous share.
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
-                            uint32_t n_tiles, int tile_log2, hipStream_t stream);
+                            uint32_t n_tiles, int tile_log2, int n_xcd, hipStream_t stream);
 
 // Enqueue steps [first_step, last_step) of a scatter + ring broadcast as one
 // launch that walks every slab of the message through those steps (all of them:

@@ -35,7 +35,7 @@ EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_static", "bcast_run_steps", "bcast_run_chain_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
     "bcast_plan_export_tiles", "bcast_plan_export_chain", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
-    "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_select_algo",
+    "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_set_xcd_count", "vbcast_select_algo",
     "bcast_plan_smp", "bcast_run_smp", "bcast_run_smp_phase", "bcast_smp_subplan",
     "bcast_plan_smp_destroy", "bcast_strerror",
 ]
@@ -106,6 +106,7 @@ def lib():
     L.vbcast_set_chain_slab_bytes.argtypes = [C.c_size_t]
     L.vbcast_set_ring_executor.argtypes = [C.c_int]
     L.vbcast_set_chain_workgroups_per_cu.argtypes = [C.c_int]
+    L.vbcast_set_xcd_count.argtypes = [C.c_int]
     L.bcast_plan_smp.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int, vp, C.POINTER(vp)]
     L.bcast_run_smp.argtypes = [vp, vp]
     L.bcast_run_smp_phase.argtypes = [vp, C.c_int, vp]
@@ -157,6 +158,10 @@ def vbcast_set_ring_executor(mode: int) -> None:
 
 def vbcast_set_chain_workgroups_per_cu(k: int) -> None:
     _check(lib().vbcast_set_chain_workgroups_per_cu(k))
+
+
+def vbcast_set_xcd_count(n_xcd: int) -> None:
+    _check(lib().vbcast_set_xcd_count(n_xcd))
 
 
 def vbcast_select_algo(nbytes: int, P: int, tuned: bool) -> int:

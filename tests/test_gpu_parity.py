@@ -260,6 +260,95 @@ def test_graph_run_final_state(V, name, algo, executor):
     comm.destroy()
 
 
+LAYOUTS_EVERY_STEP = [("P10_n512K", 16), ("P10_n512K", 48), ("P24_n4M", 112), ("P24_n4M", "mixed"),
+                      ("P24_n4M", "per_rank")]
+
+
+@pytest.mark.parametrize("executor", EXECUTORS)
+@pytest.mark.parametrize("name,layout", LAYOUTS_EVERY_STEP)
+def test_other_buffer_layouts_every_step(V, name, layout, executor):
+    """Rank buffers whose bases are 16-byte aligned but sit 16, 48 or 112 bytes
+    past a 256-byte boundary, or at different places inside their 256-byte
+    windows, or in one allocation per rank in shuffled address order: the state
+    after every step, both kernels, both schedules."""
+    w = I.workload(name)
+    rows, _keep = H.device_rows(w, layout)
+    stride = rows[0].numel()
+    assert len({r.data_ptr() % 16 for r in rows}) == 1
+    if layout != "per_rank":
+        assert any(r.data_ptr() % 256 for r in rows)
+    comm = V.Comm([r.data_ptr() for r in rows], stride)
+    for algo in ALGOS:
+        H.refill_rows(rows, w)
+        set_executor(V, executor)
+        plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+        set_executor(V, "chains")
+        sched = O.build_schedule(w.P, w.root, w.n, algo)
+        check_tables(plan, sched)
+        ref = H.host_rows(w, stride)
+        for s in range(sched.n_steps):
+            stepper(plan, executor)(s, s + 1)
+            O.apply_step(ref, sched.steps[s])
+            assert np.array_equal(H.rows_to_numpy(rows), np.stack(ref)), (name, layout, algo, executor, s)
+        H.refill_rows(rows, w)
+        V.bcast_run(plan)
+        sync()
+        want = np.stack(O.broadcast_definition(H.host_rows(w, stride), w.root, w.n))
+        assert np.array_equal(H.rows_to_numpy(rows), want), (name, layout, algo, executor, "graph")
+        plan.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("executor", EXECUTORS)
+@pytest.mark.parametrize("layout", [16, 48, 112, "mixed", "per_rank"])
+def test_other_buffer_layouts_final_state(V, layout, executor):
+    """The ragged workload (96 ranks, odd chunk size) on the same layouts: the
+    state after the scatter, in mid-ring and at the end."""
+    w = I.workload("P96_n12M_ragged")
+    rows, _keep = H.device_rows(w, layout)
+    stride = rows[0].numel()
+    comm = V.Comm([r.data_ptr() for r in rows], stride)
+    for algo in ALGOS:
+        H.refill_rows(rows, w)
+        set_executor(V, executor)
+        plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+        set_executor(V, "chains")
+        sched = O.build_schedule(w.P, w.root, w.n, algo)
+        ref = H.host_rows(w, stride)
+        done = 0
+        for stop in (sched.n_scatter_steps, sched.n_scatter_steps + 41, sched.n_steps):
+            stepper(plan, executor)(done, stop)
+            O.run_steps(ref, sched, done, stop)
+            done = stop
+            assert np.array_equal(H.rows_to_numpy(rows), np.stack(ref)), (layout, algo, executor, stop)
+        H.refill_rows(rows, w)
+        V.bcast_run(plan)
+        sync()
+        assert np.array_equal(H.rows_to_numpy(rows), np.stack(ref)), (layout, algo, executor, "graph")
+        plan.destroy()
+    comm.destroy()
+
+
+@pytest.mark.parametrize("n_xcd", [1, 2, 3, 4, 16])
+def test_other_xcd_counts(V, n_xcd):
+    """The kernels' map from workgroups to pieces of the message for other numbers
+    of accelerator dies than the device reports: still every piece exactly once."""
+    V.vbcast_set_xcd_count(n_xcd)
+    try:
+        for name in ("P24_n4M", "P96_n12M_ragged"):
+            w = I.workload(name)
+            for ex in EXECUTORS:
+                state, comm, plan = make(V, w, O.TUNED, executor=ex)
+                want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+                plan.run()
+                sync()
+                assert np.array_equal(state.cpu().numpy(), want), (name, n_xcd, ex)
+                plan.destroy()
+                comm.destroy()
+    finally:
+        V.vbcast_set_xcd_count(0)
+
+
 @pytest.mark.parametrize("tile", [4096, 8192, 32768, 65536])
 def test_other_tile_sizes(V, tile):
     w = I.workload("P24_n4M")

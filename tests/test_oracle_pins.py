@@ -245,6 +245,43 @@ def test_final_state_is_the_broadcast(P, root, n):
             assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("threads", [1, 3, 8])
+@pytest.mark.parametrize("P,root,n", [(1, 0, 5), (2, 1, 9), (8, 0, 800), (10, 4, 1003), (24, 3, 4099), (13, 12, 11)])
+def test_rows_of_a_step_over_several_cores(P, root, n, threads):
+    """The C byte execution behind the benchmark's all-cores CPU figure
+    (oracle/csrc/run_rows.c), in its literal two-phase form and in its direct
+    form: after every range of steps the buffers are the ones the plain numpy
+    execution leaves, and the end is the definition of broadcast.  The direct
+    form is only claimed for schedules whose rows are independent within a step,
+    which the C check confirms for both rings and denies for a planted overlap."""
+    from oracle import native_rows as N
+    for algo in (O.NATIVE, O.TUNED):
+        sched = O.build_schedule(P, root, n, algo)
+        assert N.rows_independent(sched.steps)
+        plain = make_bufs(P, root, n, seed=P * 77 + threads)
+        staged = [x.copy() for x in plain]
+        direct = [x.copy() for x in plain]
+        want = O.broadcast_definition(plain, root, n)
+        cuts = sorted({0, sched.n_scatter_steps, sched.n_steps // 2, sched.n_steps})
+        for a, b in zip(cuts, cuts[1:]):
+            O.run_steps(plain, sched, a, b)
+            N.run_rows(staged, sched.steps[a:b], threads, staged=True)
+            N.run_rows(direct, sched.steps[a:b], threads, staged=False)
+            for x, y, z in zip(plain, staged, direct):
+                assert np.array_equal(x, y) and np.array_equal(x, z)
+        for x, y in zip(direct, want):
+            assert np.array_equal(x, y)
+    # a step in which one row reads what another writes is not independent, and
+    # only the two-phase form then agrees with the plain execution
+    swap = [[(0, 1, 0, 8), (1, 0, 0, 8)]]
+    assert not N.rows_independent(swap)
+    bufs = [np.arange(16, dtype=np.uint8) + 16 * r for r in range(2)]
+    ref = [x.copy() for x in bufs]
+    O.apply_step(ref, swap[0])
+    N.run_rows(bufs, swap, 2, staged=True)
+    assert all(np.array_equal(x, y) for x, y in zip(bufs, ref))
+
+
 @pytest.mark.parametrize("P,root,n", [(8, 0, 800), (10, 4, 1003), (24, 3, 4099), (13, 12, 11), (16, 1, 4096)])
 def test_native_and_tuned_state_identical_after_every_step(P, root, n):
     """The tuned ring only leaves out deliveries of bytes the receiver already
