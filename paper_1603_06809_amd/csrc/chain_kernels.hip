@@ -47,6 +47,12 @@ constexpr int kThreads = 256;
 constexpr int kMinSlabLog2 = 10;   // smallest slab: one wavefront, one word per lane
 constexpr int kFillSlabLog2 = 12;  // slabs are not made smaller than this just to get more of them
 
+// Whether the whole-tile path lets the wavefronts of a workgroup take turns (one
+// wavefront copies the slab per hop) instead of sharing every hop: worth it from
+// 16 KiB slabs on, where a hop moves enough for the barrier not to matter.
+template <int TILE_LOG2, int THREADS>
+constexpr bool kTakeTurns = TILE_LOG2 >= 14 && THREADS >= 128;
+
 __device__ __forceinline__ void step_fence() {
     // Writer and reader of every byte are in the same workgroup (in fact the
     // same lane), so workgroup scope is the right one: all wavefronts of a
@@ -102,9 +108,97 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
         const uint64_t hi = lo + TILE < n ? lo + TILE : n;
         const int c0 = (int)(lo / ss);
         const int c1 = (int)((hi - 1) / ss);
-        if (c1 == c0 && hi - lo == TILE) {
-            // The common case, a whole tile inside one chunk: every lane owns the
-            // same PER_LANE words in every step, only the two buffers change.
+        if (c1 == c0 && hi - lo == TILE && kTakeTurns<TILE_LOG2, THREADS>) {
+            // A whole tile inside one chunk, slabs of 16 KiB and more: the wavefronts
+            // of the workgroup take turns.  Wavefront w copies the whole slab in the
+            // hops h with (h - first_step) mod WAVES == w, and a workgroup barrier
+            // separates consecutive hops.  The loads of a hop are then issued by
+            // another wavefront than the stores of the hop before, so they do not
+            // queue behind the acknowledgement of those stores (a wavefront's loads
+            // and stores complete through one in-order counter); a wavefront's own
+            // previous stores are WAVES - 1 hops old when it loads again, and its
+            // next chain entries arrive while the others take their turns.  Stores of
+            // one wavefront are visible to the loads another wavefront of the same
+            // workgroup issues after the barrier: they share the compute unit's L1
+            // and its in-order path to the L2 (workgroup-scope release / acquire,
+            // which in this execution mode needs no wait on the stores).
+            constexpr uint32_t WAVES = THREADS / 64;
+            constexpr int NW = (int)(TILE / 16) / 64;     // words per lane of the wavefront whose turn it is
+            constexpr int BATCH = NW < 16 ? NW : 16;      // words loaded before the first store
+            // the wavefront's number is the same in all its lanes: say so, and the turn
+            // test is a scalar branch and the chain entries come through scalar loads
+            const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+            const uint32_t lane_off = (threadIdx.x & 63u) * 16u;
+            const uint64_t *ch = chain + (size_t)c0 * hops;
+            uint32_t mine = first_step + wave;            // this wavefront's next hop
+            uint64_t e = 0, before = 0;                   // its entry, and the entry of the hop before
+            if (mine < last_step) {
+                e = ch[mine];
+                before = mine > 0 ? ch[mine - 1] : reinterpret_cast<uint64_t>(bases[root]);
+            }
+            // A hop that follows a dropped transfer (tuned ring) does not read what the
+            // hop before wrote but the copy its source rank got from the scatter
+            // [Sec. IV: that rank stopped receiving because it already held the chunk]:
+            // nothing in the last few hops feeds it, and it comes from HBM, not from
+            // cache.  The wavefront whose turn it will be issues those loads as soon as
+            // it knows - right after its previous turn, WAVES hops ahead, once the
+            // scatter hops are behind it - and only stores when its turn comes.
+            u32x4 v[BATCH];
+            bool loaded = false;   // v holds the words of hop `mine` already
+            bool fetch = false;    // the entries of hop `mine` are still to be read
+            bool early = false;    // hop `mine` reads a scatter copy: load it now
+            for (uint32_t h = first_step; h < last_step; ++h) {
+                const bool turn = h == mine;
+                if (!turn && fetch) {
+                    // read them while the next wavefront works, not before it may start
+                    fetch = false;
+                    e = ch[mine];
+                    before = ch[mine - 1];
+                    early = NW == BATCH && (before & 1) && !(e & 1) && h > (uint32_t)L;
+                }
+                const bool active = !(e & 1);
+                if constexpr (NW == BATCH) {
+                    // one place that loads, one that stores: the words stay in the same
+                    // registers whether they were loaded early or in the turn itself
+                    if ((turn && active && !loaded) || (!turn && early)) {
+                        const uint8_t *src = reinterpret_cast<const uint8_t *>(before & ~15ull) + lo;
+#pragma unroll
+                        for (int k = 0; k < BATCH; ++k) v[k] = *gmem_words(src + lane_off + k * 1024);
+                        loaded = true;
+                        early = false;
+                    }
+                    if (turn && active) {
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull) + lo;
+#pragma unroll
+                        for (int k = 0; k < BATCH; ++k) *gmem_words(dst + lane_off + k * 1024) = v[k];
+                    }
+                } else {
+                    if (turn && active) {
+                        const uint8_t *src = reinterpret_cast<const uint8_t *>(before & ~15ull) + lo;
+                        uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull) + lo;
+#pragma unroll
+                        for (int b = 0; b < NW; b += BATCH) {
+#pragma unroll
+                            for (int k = 0; k < BATCH; ++k)
+                                v[k] = *gmem_words(src + lane_off + (b + k) * 1024);
+#pragma unroll
+                            for (int k = 0; k < BATCH; ++k)
+                                *gmem_words(dst + lane_off + (b + k) * 1024) = v[k];
+                        }
+                    }
+                }
+                if (turn) {
+                    loaded = false;
+                    mine += WAVES;
+                    fetch = mine < last_step;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            }
+        } else if (c1 == c0 && hi - lo == TILE) {
+            // The common case with smaller slabs, a whole tile inside one chunk: every
+            // lane owns the same PER_LANE words in every step, only the two buffers change.
             constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t lane_off = threadIdx.x * 16u;
             const uint64_t *ch = chain + (size_t)c0 * hops;
