@@ -288,6 +288,10 @@ def main() -> int:
     ap.add_argument("--no-per-config", action="store_true")
     ap.add_argument("--init", choices=["seeded", "fast"], default="seeded",
                     help="fast: poison from one torch random fill (for profiler runs)")
+    ap.add_argument("--calibration-copy", type=float, default=0.0, metavar="GIB",
+                    help="instead of the benchmark: five plain elementwise passes by torch over "
+                         "tensors of this many GiB (dst = src + 1, every byte read once and written "
+                         "once), the copy of known size that the HBM byte counters are scaled by")
     ap.add_argument("--allocations", type=int, default=2,
                     help="the rank buffers are allocated this many times, released in between, and "
                          "the last set is used (1 = use the process's first allocation)")
@@ -306,6 +310,18 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.calibration_copy > 0:
+        nbytes = int(args.calibration_copy * 2**30) // 256 * 256
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        src.view(torch.int64).random_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration_copy_bytes_read": nbytes, "calibration_copy_bytes_written": nbytes,
+                          "passes": 5, "kernel": "torch elementwise add, uint8, out-of-place"}))
+        return 0
     V.lib()
     if args.tile_bytes:
         V.vbcast_set_tile_bytes(args.tile_bytes)

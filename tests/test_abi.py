@@ -137,3 +137,37 @@ def test_bench_runs_on_one_gpu_only():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in (r.stderr + r.stdout)
+
+
+def test_bench_reports_counter_traffic_only_for_the_profiled_kernel(tmp_path, monkeypatch):
+    """bench.py's roofline.traffic comes from the committed profile and must read
+    null as soon as the kernel source, the workload or the launch shape differ from
+    what the counters were taken on."""
+    import hashlib
+    import bench
+
+    src = tmp_path / "kernel.hip"
+    src.write_text("// kernel, first version\n")
+    sha = hashlib.sha256(src.read_bytes()).hexdigest()
+    prof = tmp_path / "profile.md"
+    prof.write_text("text\n```traffic\nworkload=W\nunit_bytes=16384\nworkgroups_per_cu=1\n"
+                    f"kernel_source_sha256={sha}\nhbm_bytes_per_launch=123456\n```\nmore text\n")
+    monkeypatch.setitem(bench.PROFILES, "chains", str(prof))
+    monkeypatch.setitem(bench.KERNEL_SOURCES, "chains", str(src))
+    assert bench.measured_traffic("chains", "W", 16384, 1)[0] == 123456.0
+    assert bench.measured_traffic("chains", "other", 16384, 1)[0] is None
+    assert bench.measured_traffic("chains", "W", 8192, 1)[0] is None
+    assert bench.measured_traffic("chains", "W", 16384, 2)[0] is None
+    src.write_text("// kernel, changed\n")
+    assert bench.measured_traffic("chains", "W", 16384, 1)[0] is None
+    prof.write_text("no block here\n")
+    assert bench.measured_traffic("chains", "W", 16384, 1) == (None, None)
+
+
+def test_committed_profiles_match_the_kernel_sources():
+    """The traffic blocks under profiles/ were taken with the kernels as they are
+    now (otherwise bench.py would silently print null)."""
+    import bench
+
+    assert bench.measured_traffic("chains", "P513_n128M", 16384, 1)[0] is not None
+    assert bench.measured_traffic("steps", "P513_n128M", 16384, 0)[0] is not None
