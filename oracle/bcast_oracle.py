@@ -155,31 +155,37 @@ def owned_after_scatter(rel: int, P: int) -> range:
 # --------------------------------------------------------------------------
 
 def tuned_switch(rel: int, P: int) -> Optional[Tuple[int, int]]:
-    """(step, flag) of the rank with relative rank ``rel``.
+    """(step, flag) of the rank with relative rank ``rel``; None for P = 1.
 
-    Scanning distances from 2**ceil(log2 P) down to 2: if the right neighbour's
-    relative rank is a multiple of the distance, the neighbour heads a subtree
-    of ``step`` chunks and this rank ends up receive-only; otherwise, if the
-    rank's own relative rank is a multiple, the rank itself heads such a
-    subtree and ends up send-only.  ``step`` is the distance, clipped so the
-    subtree does not run past the last rank.  Returns None when no distance
-    qualifies (only for P = 1, where there is no ring).
+    After the scatter some ranks are ahead of the others: the root holds the
+    whole message, and a rank whose relative rank is even heads a subtree and
+    holds its ``span`` chunks (`owned_after_scatter`).  A rank that is ahead needs
+    only ``P - span`` chunks from the ring, so it has everything ``span - 1`` steps
+    before the ring ends; from then on it takes nothing more, and its left
+    neighbour has nothing left to give it.
+
+    Seen from one rank this gives exactly one of two tails.  Of two consecutive
+    relative ranks only one is even; at the ring's seam, where the root (0)
+    follows rank P - 1, the root counts, whatever the parity of P - 1.  So:
+
+    * the right neighbour is ahead (its relative rank is even, 0 included): this
+      rank stops sending when the neighbour is complete and only receives for
+      the rest - flag RECV_ONLY, step = the neighbour's span;
+    * otherwise the rank is ahead itself: it stops receiving and only sends -
+      flag SEND_ONLY, step = its own span.
+
+    The listing of Sec. IV reaches the same pair by trying power-of-two distances
+    from 2**ceil(log2 P) down to 2, at each distance first on the right
+    neighbour, then on the rank itself; the distance at which it stops, clipped
+    at the last rank, is the span above, and the order of its two tests is what
+    gives the seam to the root.
     """
-    mask = ceil_pow2(P)
-    while mask > 1:
-        right_rel = rel + 1 if rel + 1 < P else rel + 1 - P
-        if right_rel % mask == 0:
-            step = mask
-            if right_rel + mask > P:
-                step = P - right_rel
-            return step, RECV_ONLY
-        if rel % mask == 0:
-            step = mask
-            if rel + mask > P:
-                step = P - rel
-            return step, SEND_ONLY
-        mask >>= 1
-    return None
+    if P < 2:
+        return None
+    right = (rel + 1) % P
+    if right % 2 == 0:
+        return len(owned_after_scatter(right, P)), RECV_ONLY
+    return len(owned_after_scatter(rel, P)), SEND_ONLY
 
 
 # --------------------------------------------------------------------------
@@ -196,19 +202,19 @@ class RingResult:
 def ring_steps(P: int, root: int, n: int, algo: str) -> RingResult:
     """Advance P per-rank programs through the P-1 ring steps.
 
-    Every rank keeps the cursor (j, jnext): the owner of the chunk it sends
-    next and the owner of the chunk it receives next.  It starts with its own
-    chunk and its left neighbour's, and after every step both move one rank to
-    the left, so a rank always forwards what it received one step earlier.
+    A chunk travels one rank to the right per step [Sec. III-A, Fig. 3: a rank
+    forwards what it received one step earlier]: in step i every rank passes on
+    the chunk that started i - 1 ranks to its left (its own in step 1) and
+    expects the chunk that started i ranks to its left.  Each rank decides for
+    itself what it posts; whether the posts of neighbours fit is checked below.
 
     native: every rank sends and receives in every step.
-    tuned : a rank does both while ``step <= P - i``; afterwards it only
-            receives (flag = 1) or only sends (flag = 0).
+    tuned : a rank does both for the first ``P - step`` steps; in the remaining
+            ``step - 1`` it only receives (flag RECV_ONLY) or only sends (SEND_ONLY).
     """
     if algo not in (NATIVE, TUNED):
         raise ValueError(algo)
     order = [absolute_rank(rho, root, P) for rho in range(P)]  # by relative rank
-    cursor = {r: (r, (P + r - 1) % P) for r in range(P)}
     switch = {r: tuned_switch(relative_rank(r, root, P), P) for r in range(P)}
 
     out = RingResult([], [], [])
@@ -216,28 +222,24 @@ def ring_steps(P: int, root: int, n: int, algo: str) -> RingResult:
         sends = {}   # (src, dst) -> (disp, count), posted by the sender
         recvs = {}   # (src, dst) -> (disp, count), posted by the receiver
         for r in order:
-            left = (P + r - 1) % P
+            left = (r - 1) % P
             right = (r + 1) % P
-            j, jnext = cursor[r]
-            right_disp, right_count = chunk_extent(relative_rank(j, root, P), n, P)
-            left_disp, left_count = chunk_extent(relative_rank(jnext, root, P), n, P)
+            passing = (r - (i - 1)) % P      # rank whose chunk this rank passes on
+            awaiting = (r - i) % P           # rank whose chunk it expects from the left
+            out_extent = chunk_extent(relative_rank(passing, root, P), n, P)
+            in_extent = chunk_extent(relative_rank(awaiting, root, P), n, P)
 
-            if algo == NATIVE:
-                do_send = do_recv = True
-            else:
+            sending = receiving = True
+            if algo == TUNED:
                 step, flag = switch[r]
-                if step <= P - i:
-                    do_send = do_recv = True
-                elif flag == RECV_ONLY:
-                    do_send, do_recv = False, True
-                else:
-                    do_send, do_recv = True, False
+                if i > P - step:             # the rank's one-direction tail
+                    sending = flag == SEND_ONLY
+                    receiving = flag == RECV_ONLY
 
-            if do_send:
-                sends[(r, right)] = (right_disp, right_count)
-            if do_recv:
-                recvs[(left, r)] = (left_disp, left_count)
-            cursor[r] = (jnext, (P + jnext - 1) % P)
+            if sending:
+                sends[(r, right)] = out_extent
+            if receiving:
+                recvs[(left, r)] = in_extent
 
         # Blocking point-to-point calls complete only in matched pairs.
         if sends != recvs:

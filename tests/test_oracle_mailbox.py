@@ -41,20 +41,21 @@ def rank_program(rank, P, root, n, tuned):
                 yield ("send", O.absolute_rank(rel + mask, root, P), disp, length)
         mask //= 2
 
-    # ---- ring
+    # ---- ring: a chunk moves one rank to the right per step, so in step i this
+    # rank hands on the chunk that started i - 1 ranks to its left and is handed
+    # the one that started i ranks to its left
     left, right = (rank - 1) % P, (rank + 1) % P
     sw = O.tuned_switch(rel, P)
-    j, jnext = rank, left
     for i in range(1, P):
-        sd, sc = O.chunk_extent(O.relative_rank(j, root, P), n, P)
-        rd, rc = O.chunk_extent(O.relative_rank(jnext, root, P), n, P)
-        if not tuned or sw[0] <= P - i:
-            yield ("sendrecv", right, sd, sc, left, rd, rc)
+        give = O.chunk_extent(O.relative_rank((rank - i + 1) % P, root, P), n, P)
+        take = O.chunk_extent(O.relative_rank((rank - i) % P, root, P), n, P)
+        in_tail = tuned and i > P - sw[0]
+        if not in_tail:
+            yield ("sendrecv", right, *give, left, *take)
         elif sw[1] == O.RECV_ONLY:
-            yield ("recv", left, rd, rc)
+            yield ("recv", left, *take)
         else:
-            yield ("send", right, sd, sc)
-        j, jnext = jnext, (jnext - 1) % P
+            yield ("send", right, *give)
 
 
 CASES = [(P, root, n)

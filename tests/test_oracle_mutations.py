@@ -31,28 +31,32 @@ MUTANTS = {
         "    mask = ceil_pow2(P) // 2\n    while mask >= 1:\n        rows: List[Row] = []",
         "    for mask in [1 << k for k in range(ceil_log2(P))]:\n        rows: List[Row] = []"),
     "switch: own subtree tested before the neighbour's": (
-        "        if right_rel % mask == 0:\n            step = mask\n            if right_rel + mask > P:\n                step = P - right_rel\n            return step, RECV_ONLY\n",
-        ""),
+        "    if right % 2 == 0:\n        return len(owned_after_scatter(right, P)), RECV_ONLY\n    return len(owned_after_scatter(rel, P)), SEND_ONLY",
+        "    if rel % 2 == 0:\n        return len(owned_after_scatter(rel, P)), SEND_ONLY\n    return len(owned_after_scatter(right, P)), RECV_ONLY"),
     "switch: subtree size not clipped": (
-        "            if rel + mask > P:\n                step = P - rel\n", ""),
+        "    return range(rel, min(rel + span, P))", "    return range(rel, rel + span)"),
     "switch: directions swapped": (
-        "            return step, SEND_ONLY", "            return step, RECV_ONLY"),
-    "switch: scan stops before distance 2": (
-        "    while mask > 1:\n        right_rel", "    while mask > 2:\n        right_rel"),
+        "    return len(owned_after_scatter(rel, P)), SEND_ONLY", "    return len(owned_after_scatter(rel, P)), RECV_ONLY"),
+    "switch: the root not counted as ahead": (
+        "    if right % 2 == 0:\n        return len(owned_after_scatter(right, P)), RECV_ONLY",
+        "    if right % 2 == 0 and right != 0:\n        return len(owned_after_scatter(right, P)), RECV_ONLY"),
+    "switch: span of a subtree head one level short": (
+        "    while rel % (2 * span) == 0:\n        span *= 2\n    return range(rel, min(rel + span, P))",
+        "    while rel % (4 * span) == 0:\n        span *= 2\n    return range(rel, min(rel + span, P))"),
     "ring: one-direction phase starts a step late": (
-        "if step <= P - i:", "if step <= P - i + 1:"),
+        "if i > P - step:", "if i > P - step + 1:"),
     "ring: one-direction phase starts a step early": (
-        "if step <= P - i:", "if step < P - i:"),
-    "ring: cursor walks to the right": (
-        "cursor[r] = (jnext, (P + jnext - 1) % P)", "cursor[r] = (jnext, (jnext + 1) % P)"),
+        "if i > P - step:", "if i >= P - step:"),
+    "ring: chunks counted to the right": (
+        "passing = (r - (i - 1)) % P", "passing = (r + (i - 1)) % P"),
     "ring: first chunk sent is the left neighbour's": (
-        "cursor = {r: (r, (P + r - 1) % P) for r in range(P)}",
-        "cursor = {r: ((P + r - 1) % P, (P + r - 2) % P) for r in range(P)}"),
+        "passing = (r - (i - 1)) % P      # rank whose chunk this rank passes on\n            awaiting = (r - i) % P ",
+        "passing = (r - i) % P      # rank whose chunk this rank passes on\n            awaiting = (r - i - 1) % P "),
     "ring: chunk looked up by absolute rank": (
-        "right_disp, right_count = chunk_extent(relative_rank(j, root, P), n, P)",
-        "right_disp, right_count = chunk_extent(j, n, P)"),
+        "out_extent = chunk_extent(relative_rank(passing, root, P), n, P)",
+        "out_extent = chunk_extent(passing, n, P)"),
     "ring: sends go to the left neighbour": (
-        "sends[(r, right)] = (right_disp, right_count)", "sends[(r, left)] = (right_disp, right_count)"),
+        "sends[(r, right)] = out_extent", "sends[(r, left)] = out_extent"),
     "delivery lands at the wrong offset": (
         "bufs[dst][off:off + length] = data", "bufs[dst][off - length:off] = data[:len(bufs[dst][off - length:off])]"),
     "delivery reads the receiver's buffer": (
