@@ -5,8 +5,10 @@
 // Layout of the work: one workgroup of 4 wavefronts (64 lanes each) per step,
 // lanes over the senders' relative ranks in ascending order.  Rows that exist
 // are compacted with a wavefront ballot (index inside the wave = number of set
-// bits below the lane) and an LDS exchange of the per-wave totals; the tiles
-// per row are turned into an exclusive prefix sum the same way.
+// bits below the lane), the tiles per row are turned into an exclusive prefix
+// sum with a wavefront scan, and one exchange of the per-wave totals through LDS
+// per round of 256 ranks carries both across the wavefronts, together with the
+// step's counts and byte sum.
 
 #include "vbcast_internal.h"
 
@@ -47,26 +49,6 @@ __device__ __forceinline__ T block_exclusive_scan(T v, T *slots, T &total) {
     __syncthreads();
     total = all;
     return before + incl - v;
-}
-
-// Same for a predicate: the prefix comes from a ballot instead of a scan.
-__device__ __forceinline__ uint32_t block_exclusive_count(bool pred, uint32_t *slots,
-                                                          uint32_t &total) {
-    const int w = threadIdx.x >> 6;
-    const uint64_t votes = __ballot(pred);
-    const uint32_t below = __popcll(votes & ((1ull << lane()) - 1ull));
-    if (lane() == 0) slots[w] = __popcll(votes);
-    __syncthreads();
-    uint32_t before = 0, all = 0;
-#pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-        uint32_t t = slots[k];
-        if (k < w) before += t;
-        all += t;
-    }
-    __syncthreads();
-    total = all;
-    return before + below;
 }
 
 __device__ __forceinline__ uint32_t lowbit(uint32_t x) { return x & (0u - x); }
@@ -156,8 +138,8 @@ __global__ __launch_bounds__(kThreads) void plan_descriptors(PlanArrays pa) {
 // one-launch executor.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
-    __shared__ uint32_t slots32[kWaves];
-    __shared__ uint64_t slots64[kWaves];
+    __shared__ uint32_t wave_rows[kWaves], wave_tiles[kWaves], wave_posted[kWaves], wave_mismatch[kWaves];
+    __shared__ uint64_t wave_bytes[kWaves];
 
     const int P = pa.P;
     const int s = blockIdx.x;
@@ -255,13 +237,44 @@ __global__ __launch_bounds__(kThreads) void plan_rows(PlanArrays pa) {
         uint32_t tiles_here = 0;
         if (valid) tiles_here = (uint32_t)(((off + len - 1) >> tl) - (off >> tl)) + 1u;
 
-        uint32_t rows_total, tiles_total, posted_total, mismatch_total;
-        uint64_t bytes_total;
-        const uint32_t row_idx = block_exclusive_count(valid, slots32, rows_total);
-        const uint32_t tile_before = block_exclusive_scan<uint32_t>(tiles_here, slots32, tiles_total);
-        (void)block_exclusive_count(posted, slots32, posted_total);
-        (void)block_exclusive_count(mismatch, slots32, mismatch_total);
-        (void)block_exclusive_scan<uint64_t>(valid ? len : 0, slots64, bytes_total);
+        // One exchange of wave totals through LDS serves all five quantities: the
+        // compacted row index and the tile offset need a prefix, the counts of
+        // posted sends, of disagreeing pairs and the byte sum only a total.
+        const int w = threadIdx.x >> 6;
+        const uint64_t row_votes = __ballot(valid);
+        const uint32_t row_below = __popcll(row_votes & ((1ull << lane()) - 1ull));
+        const uint32_t tile_incl = wave_inclusive_scan<uint32_t>(tiles_here);
+        uint64_t byte_sum = valid ? len : 0;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) byte_sum += __shfl_xor(byte_sum, d, 64);
+        const uint32_t posted_here = __popcll(__ballot(posted));
+        const uint32_t mismatch_here = __popcll(__ballot(mismatch));
+        if (lane() == 63) {
+            wave_rows[w] = __popcll(row_votes);
+            wave_tiles[w] = tile_incl;
+            wave_posted[w] = posted_here;
+            wave_mismatch[w] = mismatch_here;
+            wave_bytes[w] = byte_sum;
+        }
+        __syncthreads();
+        uint32_t rows_before = 0, tiles_before = 0;
+        uint32_t rows_total = 0, tiles_total = 0, posted_total = 0, mismatch_total = 0;
+        uint64_t bytes_total = 0;
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k) {
+            if (k < w) {
+                rows_before += wave_rows[k];
+                tiles_before += wave_tiles[k];
+            }
+            rows_total += wave_rows[k];
+            tiles_total += wave_tiles[k];
+            posted_total += wave_posted[k];
+            mismatch_total += wave_mismatch[k];
+            bytes_total += wave_bytes[k];
+        }
+        __syncthreads();   // the slots are written again in the next round
+        const uint32_t row_idx = rows_before + row_below;
+        const uint32_t tile_before = tiles_before + tile_incl - tiles_here;
 
         if (valid) {
             int src = rho + pa.root;
