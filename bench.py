@@ -337,10 +337,10 @@ def main() -> int:
     # One allocation per rank, as P processes would have.  How fast the same
     # kernel runs depends on which physical memory the driver hands out (a
     # write-only sweep of the buffers shows the same spread, so it is the memory,
-    # not the broadcast); the first set a fresh process gets has been the slowest
-    # in every run, the set it gets after releasing that one the fastest.  So the
-    # buffers are allocated, probed, released and allocated again, and the probe
-    # of every set is reported.
+    # not the broadcast); the first set the first process on a fresh machine gets
+    # has been the slowest in every run, the set it gets after releasing that one
+    # among the fastest.  So the buffers are allocated, probed, released and
+    # allocated again, and the probe of every set is reported.
     placement = []
     bufs = None
     for attempt in range(max(1, args.allocations)):
