@@ -921,6 +921,48 @@ def expected_rows(w, sched, k, ranks, stride):
     return out
 
 
+@pytest.mark.parametrize("slab", [32768, 65536])
+def test_large_slabs_on_a_large_message(V, slab):
+    """Slabs of 32 and 64 KiB are only kept for messages with enough of them (the
+    launch halves them otherwise): 16 ranks, 96 MiB + 12345 bytes, so that the
+    wavefront that has the turn copies its slab in several batches.  Sampled ranks
+    at sampled steps against the oracle's chunk-ownership form; then the graph,
+    every rank against the message."""
+    import torch
+    w = I.Workload(f"slab_{slab}", 16, 5, (96 << 20) + 12345, seed=4242 + slab)
+    V.vbcast_set_chain_slab_bytes(slab)
+    try:
+        state = H.device_buffers(w)
+        stride = state.shape[1]
+        comm = V.Comm([state[r].data_ptr() for r in range(w.P)], stride)
+        msg_dev = I.message_torch(w, state.device)
+        for algo in ALGOS:
+            H.refill(state, w)
+            tails_dev = state[:, w.n:].clone()
+            plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+            sched = O.build_schedule(w.P, w.root, w.n, algo)
+            nsc, S = sched.n_scatter_steps, sched.n_steps
+            done = 0
+            ranks = [w.root, (w.root + 1) % w.P, (w.root + 8) % w.P, (w.root - 1) % w.P, 0]
+            for stop in (nsc + 3, S - 2):
+                plan.run_chain_steps(done, stop)
+                done = stop
+                sync()
+                want = expected_rows(w, sched, stop, ranks, stride)
+                for r in ranks:
+                    assert np.array_equal(state[r].cpu().numpy(), want[r]), (slab, algo, stop, r)
+            H.refill(state, w)
+            V.bcast_run(plan)
+            sync()
+            assert bool(torch.equal(state[:, w.n:], tails_dev)), (slab, algo)
+            for r in range(w.P):
+                assert bool(torch.equal(state[r, : w.n], msg_dev)), (slab, algo, r)
+            plan.destroy()
+        comm.destroy()
+    finally:
+        V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
+
+
 @pytest.mark.parametrize("algo", ALGOS)
 def test_large_workload_state(V, big, algo):
     """Sampled ranks compared whole at sampled steps (state from the oracle's
