@@ -197,18 +197,23 @@ def hbm_floor_bytes(info, executor: str, algo: str) -> float:
     return float(info.bytes_moved) + float(info.n)
 
 
-def time_runs(torch, V, plan, steps: int):
-    """K graph launches between two synchronisations; an event between
-    consecutive launches (on the launch stream) gives each launch's own time."""
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+def time_runs(torch, V, plan, steps: int, each_launch: bool = True):
+    """K bcast_run calls between two synchronisations, host clock.  With
+    `each_launch` an event between consecutive calls (on the launch stream) also
+    gives each one's own time; without, nothing but the calls is enqueued (an
+    event costs a few microseconds, which shows on the short broadcasts)."""
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)] if each_launch else []
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        marks[k].record()
+        if each_launch:
+            marks[k].record()
         V.bcast_run(plan)
-    marks[steps].record()
+    if each_launch:
+        marks[steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    each = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+    each = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps)) if each_launch else []
     return dt / steps * 1e3, each
 
 
@@ -231,7 +236,8 @@ def spot_check(torch, V, I, w, bufs, plan, msg, stride: int) -> bool:
 
 def small_configs(torch, V, I, executor: str, steps: int, warmup: int):
     """The other workloads (parity-test cases, timed here for the per-(P, n)
-    table): both schedules, graph launches, the default executor."""
+    table): both schedules, bcast_run back to back, the default executor (which
+    for broadcasts this short is one kernel launch each)."""
     out = []
     for w in I.WORKLOADS[:-1]:
         stride = (w.n + 255) // 256 * 256
@@ -252,10 +258,11 @@ def small_configs(torch, V, I, executor: str, steps: int, warmup: int):
             for _ in range(warmup):
                 V.bcast_run(plan)
             torch.cuda.synchronize()
-            ms, each = time_runs(torch, V, plan, max(steps, 20))
+            ms, _ = time_runs(torch, V, plan, max(steps, 200), each_launch=False)
             floor = hbm_floor_bytes(info, executor, algo)
             rec[f"ms_{algo}"] = round(ms, 5)
             rec[f"bytes_moved_{algo}"] = int(info.bytes_moved)
+            rec["launches_per_bcast"] = int(info.run_launches)
             rec[f"algorithmic_gbs_{algo}"] = round(2.0 * info.bytes_moved / (ms * 1e-3) / 1e9, 1)
             rec[f"hbm_floor_frac_{algo}"] = round(floor / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
             plan.destroy()
@@ -407,6 +414,7 @@ def main() -> int:
             "plan_ms": round(plan_ms, 2),
             "n_steps": int(info.n_steps),
             "rows": int(info.scatter_rows + info.ring_rows),
+            "launches_per_bcast": int(info.run_launches),
             "result_ok": bool(first_ok and again_ok),
         }
         if algo == "native":
@@ -500,8 +508,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": f"{w.name}: P={w.P} virtual ranks, root={w.root}, n={w.n} bytes, "
-                        "seeded uniform random bytes; step = one tuned broadcast "
-                        "(table generation + scatter + ring, one graph launch)",
+                        "seeded uniform random bytes; step = one tuned broadcast = one bcast_run "
+                        + ("(one kernel: scatter + ring, schedule worked out in the kernel)"
+                           if tuned["launches_per_bcast"] == 1 else
+                           f"(one graph launch of {tuned['launches_per_bcast']} kernels: table generation, "
+                           "then scatter + ring)"),
             "tile_bytes": int(info.tile_bytes),
             "slab_bytes": args.slab_bytes or 16384,
             "ring_executor": executor,

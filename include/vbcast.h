@@ -78,6 +78,9 @@ enum {
 /* How bcast_run executes the ring phase (see vbcast_set_ring_executor). */
 enum { VBCAST_RING_STEPS = 0, VBCAST_RING_CHAINS = 1 };
 
+/* Where the one-launch executor takes its schedule from (see vbcast_set_chain_schedule). */
+enum { VBCAST_CHAIN_AUTO = 0, VBCAST_CHAIN_INLINE = 1, VBCAST_CHAIN_TABLES = 2 };
+
 enum {
     VBCAST_SUCCESS = 0,
     VBCAST_ERR_ARG = 1,   /* null pointer, P < 1, bad algo, bad step range, bad option */
@@ -132,11 +135,16 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
                void *hip_stream, vbcast_plan **out);
 
 /*
- * Run the whole broadcast [Sec. IV, listing: scatter, then ring]: launches the
- * plan's graph on hip_stream and returns without waiting (MPI's "blocking" is
- * the caller's stream synchronisation).  Every launch regenerates the tables
- * on the device, executes the scatter levels in order and then the ring steps
- * (see vbcast_set_ring_executor for the two ways the ring is run).
+ * Run the whole broadcast [Sec. IV, listing: scatter, then ring] on hip_stream
+ * and return without waiting (MPI's "blocking" is the caller's stream
+ * synchronisation).  Where the one-launch executor works its schedule out
+ * itself (VBCAST_RING_CHAINS with VBCAST_CHAIN_INLINE, which VBCAST_CHAIN_AUTO
+ * picks for short broadcasts; native and tuned plans) this is a single kernel
+ * launch: the kernel derives every chunk's path through the scatter tree and
+ * the ring from (P, root, n, schedule) while it copies, and no table is read.
+ * Otherwise it launches the plan's graph, which regenerates the tables on the
+ * device, then executes the scatter levels in order and then the ring steps
+ * (see vbcast_set_ring_executor and vbcast_set_chain_schedule).
  * Errors: ARG (null), HIP.
  */
 int bcast_run(const vbcast_plan *plan, void *hip_stream);
@@ -194,8 +202,9 @@ int bcast_run_steps(const vbcast_plan *plan, int first, int last, void *hip_stre
  * step earlier].  The state of the rank buffers after step first - 1 must be in
  * place (the root's message for first = 0); afterwards they hold the state after
  * step last - 1, the same as after bcast_run_steps(first, last).  With first = 0
- * and last = n_steps this is the launch the plan's graph uses.  VBCAST_NATIVE
- * and VBCAST_TUNED plans only.
+ * and last = n_steps this is the launch bcast_run makes (the plan's schedule
+ * source, see vbcast_set_chain_schedule, applies here too).  VBCAST_NATIVE and
+ * VBCAST_TUNED plans only.
  * Errors: ARG (null, other algorithm, first < 0, first > last, last > n_steps),
  * HIP.
  */
@@ -214,9 +223,11 @@ int bcast_run_steps_timed(const vbcast_plan *plan, int first, int last, void *hi
  * Run the whole broadcast once as plain launches (no graph) with events recorded
  * on hip_stream between its three phases, wait, and write the elapsed
  * milliseconds to phase_ms[0..2] (host array): table generation, scatter levels,
- * the steps after the scatter - executed the way the plan's graph executes them:
- * with VBCAST_RING_CHAINS the scatter is part of the one launch, so phase_ms[1]
- * is (close to) 0 and phase_ms[2] covers scatter and ring.  Synchronous.
+ * the steps after the scatter - executed the way bcast_run executes them: with
+ * VBCAST_RING_CHAINS the scatter is part of the one launch, so phase_ms[1] is
+ * (close to) 0 and phase_ms[2] covers scatter and ring, and with
+ * VBCAST_CHAIN_INLINE no table kernel runs either, so phase_ms[0] is (close to)
+ * 0 too.  Synchronous.
  * Errors: ARG (null), HIP.
  */
 int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms);
@@ -238,6 +249,9 @@ typedef struct vbcast_plan_info {
     uint64_t pairing_mismatches; /* ring (step, rank) pairs where the sender's and the
                                     receiver's own decisions disagree; always 0 */
     uint64_t n_tiles;            /* copy tiles over all steps */
+    uint64_t run_launches;       /* kernel launches one bcast_run makes: 1 when the one-launch
+                                    executor works its schedule out itself, else the table
+                                    kernels plus the copy kernels of the plan's graph */
 } vbcast_plan_info;
 
 /* Fill *info (host pointer) from the counts read back at plan time. */
@@ -401,6 +415,33 @@ int vbcast_set_chain_slab_bytes(size_t slab_bytes);
  * bcast_run_steps always runs whole steps.  Process-wide; ARG for other values.
  */
 int vbcast_set_ring_executor(int mode);
+
+/*
+ * Where the one-launch executor (VBCAST_RING_CHAINS) of plans created afterwards
+ * learns which buffer a chunk is copied to in each step, and which steps skip it:
+ *   VBCAST_CHAIN_INLINE  the copy kernel computes it from the chunk index: the
+ *                        chunk's path down the binomial tree [Sec. III-A], its P-1
+ *                        ring transfers, and for the tuned schedule the step from
+ *                        which the receiving rank no longer receives [Sec. IV].
+ *                        No table is read; bcast_run is that one kernel launch,
+ *                        without a graph.  Up to 1024 ranks (the kernel keeps the
+ *                        hops of the chunks it is busy with in LDS); larger
+ *                        communicators use VBCAST_CHAIN_TABLES whatever is set.
+ *   VBCAST_CHAIN_TABLES  the kernel looks it up in the chunk-major view of the step
+ *                        tables; bcast_run launches a graph of the table kernels
+ *                        followed by the copy kernel.  bcast_run_static always
+ *                        works this way.
+ *   VBCAST_CHAIN_AUTO    (default) INLINE for short broadcasts, where the two table
+ *                        kernels and the graph launch are a large part of the
+ *                        time; TABLES when every resident workgroup walks 16 or
+ *                        more slabs of the message, where they are not and where
+ *                        the lookups - scalar loads that miss their cache and come
+ *                        back after one trip to the L2 - keep a workgroup from
+ *                        issuing steps faster than the L2 answers, which measures a
+ *                        few per cent faster once the device is saturated.
+ * All copy the same rows.  Process-wide; ARG for other values.
+ */
+int vbcast_set_chain_schedule(int mode);
 
 /* Resident workgroups per compute unit for VBCAST_RING_CHAINS (1..16, default 1);
  * together with the slab size this sets how many bytes are in flight at once. */

@@ -20,16 +20,19 @@
 // end of this file.)  The message space [0, n) is cut into tile-aligned
 // slabs.  A workgroup takes a slab and walks it through all scatter levels and
 // ring steps: in a step it copies the slab's part of each chunk from the step's
-// source rank to its destination rank (the same rows the step tables hold,
-// looked up in the chunk-major "chain" view the plan writes next to them), then
+// source rank to its destination rank (the same rows the step tables hold), then
 // fences and goes on with the next step, whose source is what it has just
-// written.  Every lane re-reads from memory exactly the words it wrote one step
-// earlier; they are still in the compute unit's write-through L1 (or the XCD's
-// L2), so the only traffic that has to reach HBM is the write of every rank's
-// copy.  The resident workgroups together hold (workgroups x tile) bytes in
-// flight, sized so that a compute unit's share fits its L1; a workgroup that
-// finishes a slab takes the next one a whole grid further on, so all workgroups
-// do the same amount of work.
+// written.  Which buffer a chunk is in after a step, and whether the step moves
+// it at all, the kernel either works out itself from (P, root, n, schedule) -
+// no table is read and the broadcast is this one launch - or looks up in the
+// chunk-major "chain" view that the table kernels write next to the step tables
+// (see the two Hops types below).  Every lane re-reads from memory exactly the
+// words it wrote one step earlier; they are still in the compute unit's
+// write-through L1 (or the XCD's L2), so the only traffic that has to reach HBM
+// is the write of every rank's copy.  The resident workgroups together hold
+// (workgroups x tile) bytes in flight, sized so that a compute unit's share fits
+// its L1; a workgroup that finishes a slab takes the next one a whole grid
+// further on, so all workgroups do the same amount of work.
 //
 // Between two steps a workgroup-scope fence orders the stores of one step
 // before the loads of the next: writer and reader of every byte are the same
@@ -74,27 +77,191 @@ __device__ __forceinline__ void wait_for_loads() {
     __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
-// Where a chunk is found before step `first`: in the root's buffer before the
-// first step [Sec. III-A: the scatter starts from the root], else with whoever
-// holds it after step first - 1.
-__device__ __forceinline__ const uint8_t *chain_start(const uint64_t *ch, uint8_t *const *bases,
-                                                      int root, uint32_t first) {
-    return first == 0 ? bases[root] : reinterpret_cast<const uint8_t *>(ch[first - 1] & ~15ull);
+__device__ __forceinline__ uint32_t lowbit(uint32_t x) { return x & (0u - x); }
+
+// Two ways to know the hops of a chunk's chain.  Both answer, for the chunk with
+// relative index c and step s (scatter levels 0..L-1, then ring steps):
+//   entry(c, s)   the buffer that holds the chunk after step s, with bit 0 set
+//                 when step s has no transfer for this chunk (it is not on the
+//                 chunk's tree path at that level, the tuned ring drops it, or the
+//                 chunk is empty) - buffers are 16-byte aligned, the bit is free;
+//   source(c, s)  the buffer step s reads the chunk from: the root's before the
+//                 first step [Sec. III-A: the scatter starts from the root], else
+//                 the holder after step s - 1;
+//   chunk_begin(c) the chunk's byte offset in the message.
+// prepare(...) is called by all threads of a workgroup before it walks a slab (by
+// all lanes of a wavefront before it walks a chunk, in the small-chunk kernel) and
+// names the chunks that entry() will be asked about until the next prepare.
+
+// Worked out by the kernel itself.  Scatter level t has distance m = 2^(L-1-t):
+// chunk c rides the message from its subtree's root (c with the bits below 2m
+// cleared) to that root + m iff bit m of c is set, and afterwards sits at c with
+// the bits below m cleared [Sec. III-A, Figs. 1-2].  Ring step i passes chunk c
+// from relative rank c + i - 1 to c + i [Sec. III-A, Fig. 3].  The tuned ring
+// leaves that transfer out once the receiver has begun to get back what it has
+// held since the scatter [Sec. IV]: relative rank r came out of the scatter with
+// span(r) chunks - all P for the root, else the largest power of two dividing r,
+// cut at the end of the ranks - and the last span(r) - 1 chunks the ring would
+// bring it are those, so it receives in steps i <= P - span(r) only.
+//
+// The hops of a chunk are computed when a workgroup turns to a slab of that
+// chunk, one hop per lane, and kept in LDS while the slab is walked: a step then
+// gets its entry with one LDS read instead of a chain of scalar arithmetic that
+// would sit in the dependent path of every step.  The rank buffers' addresses
+// are copied to LDS once per workgroup, so that computing a chunk's hops reads
+// no memory at all (a load from memory waits behind the kernel's own stores).
+struct InlineHops {
+    // LDS words: the rank buffers, then `chunks` sets of entries
+    static constexpr int lds_words(int chunks) { return kInlineMaxRanks + chunks * kInlineMaxHops; }
+
+    uint8_t *const *bases;   // [P] rank buffers, by absolute rank
+    int P, L, root;
+    bool tuned;
+    uint64_t n, ss;
+    const uint64_t *rank_buffer;   // LDS copy of bases
+    uint64_t *first_slots;   // LDS: entries of chunk `first_chunk`, indexed by step
+    uint64_t *other_slots;   // LDS: entries of the other chunk prepared (if any)
+    int first_chunk;
+
+    __device__ __forceinline__ static InlineHops make(const uint64_t *, const uint64_t *,
+                                                       uint8_t *const *bases, int P, int L, int root,
+                                                       int tuned, uint64_t n, uint64_t ss) {
+        return InlineHops{bases, P, L, root, tuned != 0, n, ss, nullptr, nullptr, nullptr, -1};
+    }
+    // All threads of the workgroup, once, before anything else: `lds` = lds_words(..) words.
+    __device__ __forceinline__ void begin(uint64_t *lds) {
+        for (int r = threadIdx.x; r < P; r += blockDim.x) lds[r] = reinterpret_cast<uint64_t>(bases[r]);
+        rank_buffer = lds;
+        __syncthreads();
+    }
+    __device__ __forceinline__ uint64_t chunk_begin(int c) const {
+        const uint64_t at = (uint64_t)c * ss;
+        return at < n ? at : n;
+    }
+    __device__ __forceinline__ uint64_t compute(int c, uint32_t s) const {
+        int holder;   // relative rank
+        bool moves;
+        if (s < (uint32_t)L) {
+            const int m = 1 << (L - 1 - (int)s);
+            holder = c & ~(m - 1);
+            moves = (c & m) != 0;
+        } else {
+            const int i = (int)s - L + 1;
+            holder = c + i;
+            if (holder >= P) holder -= P;
+            int span = P;
+            if (holder != 0) {
+                span = (int)lowbit((uint32_t)holder);
+                if (span > P - holder) span = P - holder;
+            }
+            moves = !tuned || span <= P - i;
+        }
+        if ((uint64_t)c * ss >= n) moves = false;   // an empty chunk
+        int rank = holder + root;
+        if (rank >= P) rank -= P;
+        return rank_buffer[rank] | (moves ? 0ull : 1ull);
+    }
+    // Entries of steps [first_step - 1, last_step) of `c` into `slots`, one step per
+    // lane of the `lanes` lanes that call this together (`lane` = 0..lanes-1).
+    __device__ __forceinline__ void fill(uint64_t *slots, int c, uint32_t first_step,
+                                         uint32_t last_step, uint32_t lane, uint32_t lanes) const {
+        for (uint32_t s = (first_step ? first_step - 1 : 0) + lane; s < last_step; s += lanes)
+            slots[s] = compute(c, s);
+    }
+    // Workgroup: the one or two chunks of the next slab (`lds` as given to begin,
+    // two sets of entries).
+    __device__ __forceinline__ void prepare(uint64_t *lds, int c0, int c1, uint32_t first_step,
+                                            uint32_t last_step) {
+        __syncthreads();   // nobody reads the previous slab's entries any more
+        first_slots = lds + kInlineMaxRanks;
+        other_slots = first_slots + kInlineMaxHops;
+        first_chunk = c0;
+        fill(first_slots, c0, first_step, last_step, threadIdx.x, blockDim.x);
+        if (c1 != c0) fill(other_slots, c1, first_step, last_step, threadIdx.x, blockDim.x);
+        __syncthreads();
+    }
+    // Wavefront `wave` of the workgroup: its one chunk (`lds` as given to begin, one
+    // set of entries per wavefront).  A wavefront's LDS accesses are carried out in
+    // the order it issues them, so its own reads see its writes.
+    __device__ __forceinline__ void prepare_wave(uint64_t *lds, uint32_t wave, int c,
+                                                 uint32_t first_step, uint32_t last_step) {
+        first_slots = other_slots = lds + kInlineMaxRanks + (size_t)wave * kInlineMaxHops;
+        first_chunk = c;
+        fill(first_slots, c, first_step, last_step, threadIdx.x & 63u, 64u);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    // (c, s) is the same in all lanes of the calling wavefront, everywhere in this
+    // file: say so, and what is done with the entry stays scalar.
+    __device__ __forceinline__ uint64_t entry(int c, uint32_t s) const {
+        const uint64_t v = (c == first_chunk ? first_slots : other_slots)[s];
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return ((uint64_t)hi << 32) | lo;
+    }
+    __device__ __forceinline__ uint64_t source(int c, uint32_t s) const {
+        return s == 0 ? reinterpret_cast<uint64_t>(bases[root]) : entry(c, s - 1);
+    }
+};
+
+// Looked up in what the table kernels wrote: chain[c * hops + s] is entry(c, s),
+// chunk_off[c] the chunk's offset.  The lookups are scalar loads that miss the
+// scalar cache (the table is far larger) and return after one trip to the L2
+// and back on a path of their own, not behind the compute unit's stores.  Where
+// the wavefronts take turns, the wavefront that has just had its turn waits for
+// such a load before it rejoins the barrier, so a workgroup starts a step no
+// sooner than the L2 answers a read - a little slower when the device is
+// otherwise idle, a few per cent faster when all compute units stream at once
+// (measured: the same kernel with the entries in LDS, which come back at once,
+// loses 3-4 % on a 64 GiB broadcast and wins on short ones).
+struct TableHops {
+    const uint64_t *chain;
+    const uint64_t *chunk_off;
+    uint8_t *const *bases;
+    size_t hops;             // L + P - 1 entries per chunk
+    int root;
+
+    __device__ __forceinline__ static TableHops make(const uint64_t *chain, const uint64_t *chunk_off,
+                                                      uint8_t *const *bases, int P, int L, int root,
+                                                      int, uint64_t, uint64_t) {
+        return TableHops{chain, chunk_off, bases, (size_t)L + (size_t)P - 1, root};
+    }
+    static constexpr int lds_words(int) { return 1; }
+    __device__ __forceinline__ uint64_t chunk_begin(int c) const { return chunk_off[c]; }
+    __device__ __forceinline__ void begin(uint64_t *) {}
+    __device__ __forceinline__ void prepare(uint64_t *, int, int, uint32_t, uint32_t) {}
+    __device__ __forceinline__ void prepare_wave(uint64_t *, uint32_t, int, uint32_t, uint32_t) {}
+    __device__ __forceinline__ uint64_t entry(int c, uint32_t s) const {
+        return chain[(size_t)c * hops + s];
+    }
+    __device__ __forceinline__ uint64_t source(int c, uint32_t s) const {
+        return s == 0 ? reinterpret_cast<uint64_t>(bases[root]) : entry(c, s - 1);
+    }
+};
+
+__device__ __forceinline__ const uint8_t *buffer_of(uint64_t entry) {
+    return reinterpret_cast<const uint8_t *>(entry & ~15ull);
 }
 
-// chain[c * (L + P - 1) + s]: the buffer that holds chunk c after step s (scatter
-// levels first, then ring steps); bit 0 set = step s has no row for this chunk
-// (not on its tree path at that level, dropped by the tuned ring, or empty).
-template <int TILE_LOG2, int THREADS>
+// Steps [first_step, last_step) of every slab of the message.  `chain` and
+// `chunk_off` are read only by TableHops, `tuned` only by InlineHops.  The
+// pointers are separate restrict-qualified kernel arguments on purpose: that is
+// what lets the compiler fetch entries and buffer addresses with scalar loads
+// although the kernel stores through pointers it has loaded.
+template <int TILE_LOG2, int THREADS, class Hops>
 __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict__ chain,
                                                        const uint64_t *__restrict__ chunk_off,
                                                        uint8_t *const *__restrict__ bases, int P,
-                                                       int L, int root, uint64_t n, uint64_t ss,
-                                                       uint32_t n_slabs, uint32_t xcd_run,
-                                                       uint32_t n_xcd, uint32_t first_step,
-                                                       uint32_t last_step) {
+                                                       int L, int root, int tuned, uint64_t n,
+                                                       uint64_t ss, uint32_t n_slabs,
+                                                       uint32_t xcd_run, uint32_t n_xcd,
+                                                       uint32_t first_step, uint32_t last_step) {
+    __shared__ uint64_t hop_slots[Hops::lds_words(2)];
+    Hops hops = Hops::make(chain, chunk_off, bases, P, L, root, tuned, n, ss);
+    hops.begin(hop_slots);
+    const uint32_t scatter_hops = (uint32_t)L;
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
-    const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
     // Workgroups are handed to the XCDs round-robin (workgroup id mod n_xcd).
     // Give each XCD runs of `xcd_run` consecutive slabs (64 KiB) instead of every
     // n-th slab, so that the addresses one XCD touches spread over all of its L2
@@ -108,6 +275,7 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
         const uint64_t hi = lo + TILE < n ? lo + TILE : n;
         const int c0 = (int)(lo / ss);
         const int c1 = (int)((hi - 1) / ss);
+        hops.prepare(hop_slots, c0, c1, first_step, last_step);
         if (c1 == c0 && hi - lo == TILE && kTakeTurns<TILE_LOG2, THREADS>) {
             // A whole tile inside one chunk, slabs of 16 KiB and more: the wavefronts
             // of the workgroup take turns.  Wavefront w copies the whole slab in the
@@ -126,15 +294,14 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             constexpr int NW = (int)(TILE / 16) / 64;     // words per lane of the wavefront whose turn it is
             constexpr int BATCH = NW < 16 ? NW : 16;      // words loaded before the first store
             // the wavefront's number is the same in all its lanes: say so, and the turn
-            // test is a scalar branch and the chain entries come through scalar loads
+            // test is a scalar branch and the chain entries are scalar values
             const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
             const uint32_t lane_off = (threadIdx.x & 63u) * 16u;
-            const uint64_t *ch = chain + (size_t)c0 * hops;
             uint32_t mine = first_step + wave;            // this wavefront's next hop
             uint64_t e = 0, before = 0;                   // its entry, and the entry of the hop before
             if (mine < last_step) {
-                e = ch[mine];
-                before = mine > 0 ? ch[mine - 1] : reinterpret_cast<uint64_t>(bases[root]);
+                e = hops.entry(c0, mine);
+                before = hops.source(c0, mine);
             }
             // A hop that follows a dropped transfer (tuned ring) does not read what the
             // hop before wrote but the copy its source rank got from the scatter
@@ -152,9 +319,9 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                 if (!turn && fetch) {
                     // read them while the next wavefront works, not before it may start
                     fetch = false;
-                    e = ch[mine];
-                    before = ch[mine - 1];
-                    early = NW == BATCH && (before & 1) && !(e & 1) && h > (uint32_t)L;
+                    e = hops.entry(c0, mine);
+                    before = hops.source(c0, mine);
+                    early = NW == BATCH && (before & 1) && !(e & 1) && h > scatter_hops;
                 }
                 const bool active = !(e & 1);
                 if constexpr (NW == BATCH) {
@@ -201,17 +368,20 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             // lane owns the same PER_LANE words in every step, only the two buffers change.
             constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t lane_off = threadIdx.x * 16u;
-            const uint64_t *ch = chain + (size_t)c0 * hops;
-            const uint8_t *src = chain_start(ch, bases, root, first_step) + lo;
-            uint64_t e = ch[first_step];
-            for (size_t i = first_step + 1; i <= last_step; ++i) {
-                const uint64_t nxt = ch[i < last_step ? i : first_step];  // next step's entry, early
+            const uint8_t *src = buffer_of(hops.source(c0, first_step)) + lo;
+            uint64_t e = hops.entry(c0, first_step);
+            for (uint32_t i = first_step + 1; i <= last_step; ++i) {
                 uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull) + lo;
-                if (!(e & 1)) {
-                    u32x4 v[PER_LANE];
+                const bool moves = !(e & 1);
+                u32x4 v[PER_LANE];
+                if (moves) {
 #pragma unroll
                     for (int k = 0; k < PER_LANE; ++k)
                         v[k] = *gmem_words(src + lane_off + k * (THREADS * 16));
+                }
+                // the next step's entry, while the loads are under way
+                const uint64_t nxt = hops.entry(c0, i < last_step ? i : first_step);
+                if (moves) {
 #pragma unroll
                     for (int k = 0; k < PER_LANE; ++k)
                         *gmem_words(dst + lane_off + k * (THREADS * 16)) = v[k];
@@ -229,11 +399,9 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             // per byte (lanes 0-15 and 16-31).
             constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t tid = threadIdx.x;
-            const uint64_t cut = c1 > c0 ? chunk_off[c1] : hi;   // A = [lo, cut), B = [cut, hi)
-            const uint64_t *chA = chain + (size_t)c0 * hops;
-            const uint64_t *chB = chain + (size_t)c1 * hops;
-            const uint8_t *srcA = chain_start(chA, bases, root, first_step);
-            const uint8_t *srcB = chain_start(chB, bases, root, first_step);
+            const uint64_t cut = c1 > c0 ? hops.chunk_begin(c1) : hi;   // A = [lo, cut), B = [cut, hi)
+            const uint8_t *srcA = buffer_of(hops.source(c0, first_step));
+            const uint8_t *srcB = buffer_of(hops.source(c1, first_step));
 
             uint64_t word_at[PER_LANE];
             bool word_a[PER_LANE], word_b[PER_LANE];
@@ -251,12 +419,12 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
             const bool byte_a = byte_lane && byte_at < cut;
             const bool byte_b = byte_lane && byte_at >= cut;
 
-            uint64_t eA = chA[first_step];
-            uint64_t eB = chB[first_step];
-            for (size_t i = first_step + 1; i <= last_step; ++i) {
-                const size_t nx = i < last_step ? i : first_step;  // the next step's entries, early
-                const uint64_t nA = chA[nx];
-                const uint64_t nB = chB[nx];
+            uint64_t eA = hops.entry(c0, first_step);
+            uint64_t eB = hops.entry(c1, first_step);
+            for (uint32_t i = first_step + 1; i <= last_step; ++i) {
+                const uint32_t nx = i < last_step ? i : first_step;  // the next step's entries, early
+                const uint64_t nA = hops.entry(c0, nx);
+                const uint64_t nB = hops.entry(c1, nx);
                 uint8_t *dA = reinterpret_cast<uint8_t *>(eA & ~15ull);
                 uint8_t *dB = reinterpret_cast<uint8_t *>(eB & ~15ull);
                 const bool runA = !(eA & 1), runB = !(eB & 1);
@@ -293,18 +461,22 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
 // independent: a lane only ever re-reads what it wrote itself.  Lanes 0-15 also
 // take the bytes before the chunk's first 16-byte boundary, lanes 16-31 the bytes
 // after its last one.
+template <class Hops>
 __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__restrict__ chain,
                                                              const uint64_t *__restrict__ chunk_off,
                                                              uint8_t *const *__restrict__ bases,
-                                                             int P, int L, int root,
+                                                             int P, int L, int root, int tuned,
+                                                             uint64_t n, uint64_t ss,
                                                              uint32_t first_step, uint32_t last_step) {
-    const size_t hops = (size_t)L + (size_t)P - 1;   // scatter levels, then ring steps
-    // the chunk is the same for all lanes of a wavefront: say so, and its chain
-    // entries come through scalar loads
+    __shared__ uint64_t hop_slots[Hops::lds_words(kThreads / 64)];
+    Hops hops = Hops::make(chain, chunk_off, bases, P, L, root, tuned, n, ss);
+    hops.begin(hop_slots);
+    // the chunk is the same for all lanes of a wavefront: say so, and what depends
+    // on it alone stays in scalar registers
     const int c = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kThreads / 64) + (threadIdx.x / 64)));
     if (c >= P) return;
     const uint32_t lane = threadIdx.x % 64;
-    const uint64_t a = chunk_off[c], b = chunk_off[c + 1];
+    const uint64_t a = hops.chunk_begin(c), b = hops.chunk_begin(c + 1);
     if (a >= b) return;
     uint64_t body = (a + 15) & ~15ull;
     if (body > b) body = b;
@@ -317,11 +489,11 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
     const bool word_lane = lane < (uint32_t)((tail - body) >> 4);   // fewer than 64 words
     const uint64_t word_at = body + (uint64_t)lane * 16u;
 
-    const uint64_t *ch = chain + (size_t)c * hops;
-    const uint8_t *src = chain_start(ch, bases, root, first_step);
-    uint64_t e = ch[first_step];
-    for (size_t i = first_step + 1; i <= last_step; ++i) {
-        const uint64_t nxt = ch[i < last_step ? i : first_step];
+    hops.prepare_wave(hop_slots, threadIdx.x / 64, c, first_step, last_step);
+    const uint8_t *src = buffer_of(hops.source(c, first_step));
+    uint64_t e = hops.entry(c, first_step);
+    for (uint32_t i = first_step + 1; i <= last_step; ++i) {
+        const uint64_t nxt = hops.entry(c, i < last_step ? i : first_step);
         uint8_t *dst = reinterpret_cast<uint8_t *>(e & ~15ull);
         if (!(e & 1)) {
             u32x4 v;
@@ -338,13 +510,13 @@ __global__ __launch_bounds__(kThreads) void ring_chain_small(const uint64_t *__r
     }
 }
 
-}  // namespace
-
-hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
-                             int last_step, hipStream_t stream) {
+template <class Hops>
+hipError_t launch_with(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
+                       int last_step, hipStream_t stream) {
     if (pa.n == 0 || pa.P < 2 || first_step >= last_step) return hipSuccess;
     if (first_step < 0 || last_step > pa.n_steps) return hipErrorInvalidValue;
     const uint32_t s0 = (uint32_t)first_step, s1 = (uint32_t)last_step;
+    const int tuned = pa.algo == kAlgoTuned ? 1 : 0;
     // Slab size: the plan's slab size, halved (with twice the workgroups, so the
     // bytes in flight stay the same)
     //  - while a slab is longer than a chunk: it must not hold more than one chunk
@@ -372,9 +544,9 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, in
     if ((1ull << tl) > pa.ss) {
         // chunks shorter than 1 KiB: one wavefront per chunk
         const uint32_t per_wg = kThreads / 64;
-        hipLaunchKernelGGL(ring_chain_small, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
+        hipLaunchKernelGGL(ring_chain_small<Hops>, dim3(((uint32_t)pa.P + per_wg - 1) / per_wg),
                            dim3(kThreads), 0, stream, pa.chain, pa.chunk_off, pa.bases, pa.P, pa.L,
-                           pa.root, s0, s1);
+                           pa.root, tuned, pa.n, pa.ss, s0, s1);
         return hipGetLastError();
     }
     const uint64_t n_slabs64 = (pa.n + (1ull << tl) - 1) >> tl;
@@ -389,8 +561,9 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, in
     const dim3 g(grid);
     // one 16-byte word per lane in the two smallest slabs, so fewer lanes there
 #define VB_LAUNCH(TL, LANES)                                                                 \
-    hipLaunchKernelGGL((ring_chain<TL, LANES>), g, dim3(LANES), 0, stream, pa.chain,         \
-                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, pa.n, pa.ss, n_slabs, xcd_run, n_xcd, s0, s1)
+    hipLaunchKernelGGL((ring_chain<TL, LANES, Hops>), g, dim3(LANES), 0, stream, pa.chain,   \
+                       pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, tuned, pa.n, pa.ss, n_slabs,  \
+                       xcd_run, n_xcd, s0, s1)
     switch (tl) {
         case 10: VB_LAUNCH(10, 64); break;
         case 11: VB_LAUNCH(11, 128); break;
@@ -403,6 +576,16 @@ hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, in
     }
 #undef VB_LAUNCH
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
+                             int last_step, bool from_tables, hipStream_t stream) {
+    if (pa.algo != kAlgoNative && pa.algo != kAlgoTuned) return hipErrorInvalidValue;
+    if (!from_tables && pa.P > kInlineMaxRanks) return hipErrorInvalidValue;
+    return from_tables ? launch_with<TableHops>(pa, wgs_at_plan_tile, first_step, last_step, stream)
+                       : launch_with<InlineHops>(pa, wgs_at_plan_tile, first_step, last_step, stream);
 }
 
 }  // namespace vbcast

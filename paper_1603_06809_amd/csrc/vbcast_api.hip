@@ -36,7 +36,8 @@ struct vbcast_plan {
     // per-step counts, read back once at plan time
     std::vector<uint32_t> step_rows, step_tiles, step_posted, step_mismatch;
     std::vector<uint64_t> step_bytes;
-    int ring_executor = VBCAST_RING_CHAINS;  // what the graph uses for the ring phase
+    int ring_executor = VBCAST_RING_CHAINS;  // what bcast_run uses for the ring phase
+    bool chain_from_tables = false;          // one-launch executor: hops looked up, not derived
     uint32_t chain_grid = 0;                 // workgroups of the one-launch ring
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
@@ -66,6 +67,7 @@ thread_local std::string g_text;
 std::atomic<int> g_tile_log2{14};
 std::atomic<int> g_slab_log2{14};
 std::atomic<int> g_ring_executor{VBCAST_RING_CHAINS};
+std::atomic<int> g_chain_schedule{VBCAST_CHAIN_AUTO};
 std::atomic<int> g_chain_wgs_per_cu{1};
 std::atomic<int> g_xcd_override{0};  // 0 = ask the device
 
@@ -203,6 +205,10 @@ bool one_launch(const vbcast_plan *plan) {
     return (a == VBCAST_NATIVE || a == VBCAST_TUNED) && plan->ring_executor == VBCAST_RING_CHAINS;
 }
 
+// The whole broadcast is one kernel that reads no table: bcast_run launches it
+// as it is, and the plan has no graph.
+bool single_kernel(const vbcast_plan *plan) { return one_launch(plan) && !plan->chain_from_tables; }
+
 // The scatter levels, the way the plan's graph runs them: step by step, or not at
 // all when the one-launch executor carries them together with the ring.
 int launch_scatter(const vbcast_plan *plan, hipStream_t stream) {
@@ -217,7 +223,8 @@ int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
     if (one_launch(plan)) {
-        hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, 0, pa.n_steps, stream);
+        hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, 0, pa.n_steps,
+                                                 plan->chain_from_tables, stream);
         if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
         return VBCAST_SUCCESS;
     }
@@ -231,6 +238,7 @@ int graph_tile_map_steps(const vbcast_plan *plan) {
 }
 
 int build_graph(vbcast_plan *plan) {
+    if (single_kernel(plan)) return VBCAST_SUCCESS;   // nothing to chain
     hipStream_t cap = nullptr;
     HIP_TRY(hipStreamCreateWithFlags(&cap, hipStreamNonBlocking));
     int rc = VBCAST_SUCCESS;
@@ -240,8 +248,9 @@ int build_graph(vbcast_plan *plan) {
         return hip_fail(e, "hipStreamBeginCapture");
     }
     const PlanArrays &pa = plan->pa;
-    // The one-launch executor reads the chain view, not tile maps: its graph does
-    // not rebuild them (they were built at plan time for bcast_run_steps).
+    // The one-launch executor, when it looks its hops up, reads the chain view, not
+    // tile maps: its graph does not rebuild them (they were built at plan time for
+    // bcast_run_steps).
     e = vbcast::launch_plan_kernels(pa, graph_tile_map_steps(plan), cap);
     if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
     if (rc == VBCAST_SUCCESS) rc = launch_scatter(plan, cap);
@@ -292,6 +301,13 @@ int vbcast_set_chain_slab_bytes(size_t slab_bytes) {
 int vbcast_set_ring_executor(int mode) {
     if (mode != VBCAST_RING_STEPS && mode != VBCAST_RING_CHAINS) return VBCAST_ERR_ARG;
     g_ring_executor.store(mode);
+    return VBCAST_SUCCESS;
+}
+
+int vbcast_set_chain_schedule(int mode) {
+    if (mode != VBCAST_CHAIN_AUTO && mode != VBCAST_CHAIN_INLINE && mode != VBCAST_CHAIN_TABLES)
+        return VBCAST_ERR_ARG;
+    g_chain_schedule.store(mode);
     return VBCAST_SUCCESS;
 }
 
@@ -420,6 +436,15 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     pa.bases = comm->dev_bases;
     plan->ring_executor = g_ring_executor.load();
     plan->chain_grid = (uint32_t)comm->compute_units * (uint32_t)g_chain_wgs_per_cu.load();
+    {
+        // AUTO: look the hops up once every resident workgroup has 16 or more slabs of
+        // the message to walk (see vbcast_set_chain_schedule), else work them out
+        const int mode = g_chain_schedule.load();
+        const uint64_t slabs = (n + (uint64_t(1) << pa.slab_log2) - 1) >> pa.slab_log2;
+        const bool long_run = slabs >= 16ull * plan->chain_grid;
+        plan->chain_from_tables = mode == VBCAST_CHAIN_TABLES || P > vbcast::kInlineMaxRanks ||
+                                  (mode == VBCAST_CHAIN_AUTO && long_run);
+    }
 
     int rc = VBCAST_SUCCESS;
     e = vbcast::launch_plan_kernels(pa, pa.n_steps, stream);
@@ -461,7 +486,9 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
 }
 
 int bcast_run(const vbcast_plan *plan, void *hip_stream) {
-    if (!plan || !plan->exec) return VBCAST_ERR_ARG;
+    if (!plan) return VBCAST_ERR_ARG;
+    if (single_kernel(plan)) return launch_ring(plan, static_cast<hipStream_t>(hip_stream));
+    if (!plan->exec) return VBCAST_ERR_ARG;
     HIP_TRY(hipGraphLaunch(plan->exec, static_cast<hipStream_t>(hip_stream)));
     return VBCAST_SUCCESS;
 }
@@ -498,7 +525,7 @@ int bcast_run_static(const vbcast_comm *comm, size_t count, size_t dtype_size, i
     if (e != hipSuccess) return hip_fail(e, "plan kernels");
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
     const uint32_t grid = (uint32_t)comm->compute_units * (uint32_t)g_chain_wgs_per_cu.load();
-    e = vbcast::launch_ring_chain(pa, grid, 0, pa.n_steps, stream);
+    e = vbcast::launch_ring_chain(pa, grid, 0, pa.n_steps, /*from_tables=*/true, stream);
     if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
     return VBCAST_SUCCESS;
 }
@@ -515,6 +542,7 @@ int bcast_run_chain_steps(const vbcast_plan *plan, int first, int last, void *hi
     if (pa.algo != VBCAST_NATIVE && pa.algo != VBCAST_TUNED) return VBCAST_ERR_ARG;
     if (first < 0 || first > last || last > pa.n_steps) return VBCAST_ERR_ARG;
     hipError_t e = vbcast::launch_ring_chain(pa, plan->chain_grid, first, last,
+                                             plan->chain_from_tables,
                                              static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "ring chain kernel");
     return VBCAST_SUCCESS;
@@ -575,7 +603,7 @@ int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms) 
         if (e != hipSuccess) rc = hip_fail(e, "hipEventRecord");
     };
     mark(0);
-    if (rc == VBCAST_SUCCESS) {
+    if (rc == VBCAST_SUCCESS && !single_kernel(plan)) {
         hipError_t e = vbcast::launch_plan_kernels(plan->pa, graph_tile_map_steps(plan), stream);
         if (e != hipSuccess) rc = hip_fail(e, "plan kernels");
     }
@@ -619,6 +647,15 @@ int bcast_plan_info(const vbcast_plan *plan, vbcast_plan_info *info) {
         info->n_tiles += plan->step_tiles[s];
     }
     info->bytes_moved = info->scatter_bytes + info->ring_bytes;
+    const bool copies = pa.n_steps > 0 && pa.n > 0;
+    if (single_kernel(plan)) {
+        info->run_launches = copies ? 1 : 0;
+    } else if (one_launch(plan)) {
+        info->run_launches = pa.n_steps > 0 ? 2 + (copies ? 1 : 0) : 1;   // descriptors, rows, copy
+    } else {
+        info->run_launches = pa.n_steps > 0 ? 3 : 1;                      // descriptors, rows, tile maps
+        for (int s = 0; s < pa.n_steps; ++s) info->run_launches += plan->step_tiles[s] > 0 ? 1 : 0;
+    }
     return VBCAST_SUCCESS;
 }
 
@@ -791,7 +828,8 @@ int bcast_plan_smp(const vbcast_comm *comm, size_t count, size_t dtype_size, int
     for (int j = 0; j < n_nodes; ++j)
         if (j != root_node) add(3, node_ranks(j), 0, VBCAST_BINOMIAL);
 
-    // one graph: every sub-plan's table kernels and steps, in order
+    // one graph: every sub-plan's table kernels (where its executor reads tables) and
+    // steps, in order
     if (rc == VBCAST_SUCCESS) {
         hipStream_t cap = nullptr;
         hipError_t e = hipStreamCreateWithFlags(&cap, hipStreamNonBlocking);
@@ -802,8 +840,10 @@ int bcast_plan_smp(const vbcast_comm *comm, size_t count, size_t dtype_size, int
             if (rc == VBCAST_SUCCESS) {
                 for (auto &sub : sp->subs) {
                     const vbcast_plan *p = sub.plan;
-                    e = vbcast::launch_plan_kernels(p->pa, graph_tile_map_steps(p), cap);
-                    if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
+                    if (!single_kernel(p)) {
+                        e = vbcast::launch_plan_kernels(p->pa, graph_tile_map_steps(p), cap);
+                        if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
+                    }
                     if (rc == VBCAST_SUCCESS) rc = launch_scatter(p, cap);
                     if (rc == VBCAST_SUCCESS) rc = launch_ring(p, cap);
                     if (rc != VBCAST_SUCCESS) break;

@@ -94,12 +94,22 @@ hipError_t launch_plan_census(const PlanArrays &pa, int ranks_per_node, hipStrea
 hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *bases,
                             uint32_t n_tiles, int tile_log2, int n_xcd, hipStream_t stream);
 
-// Enqueue steps [first_step, last_step) of a scatter + ring broadcast as one
-// launch that walks every slab of the message through those steps (all of them:
-// 0 and pa.n_steps).  `wgs_at_plan_tile` persistent workgroups would share the
-// slabs at the plan's slab size; the launch may pick a smaller slab (and
-// proportionally more workgroups) or one wavefront per chunk for short chunks.
+// Most ranks a broadcast may have for the one-launch kernel to work its hops out
+// itself: it keeps the rank buffers' addresses and the hops of the chunks it is
+// busy with in LDS, 8 bytes per rank and per step (ceil(log2 P) + P - 1 steps).
+constexpr int kInlineMaxRanks = 1024;
+constexpr int kInlineMaxHops = 1040;   // >= 10 + 1023
+
+// Enqueue steps [first_step, last_step) of a scatter + ring broadcast (native or
+// tuned) as one launch that walks every slab of the message through those steps
+// (all of them: 0 and pa.n_steps).  `wgs_at_plan_tile` persistent workgroups
+// would share the slabs at the plan's slab size; the launch may pick a smaller
+// slab (and proportionally more workgroups) or one wavefront per chunk for short
+// chunks.  With `from_tables` the kernel looks the hops up in pa.chain and
+// pa.chunk_off, which launch_plan_kernels must have filled on this stream before;
+// without, it derives them itself from pa.P, pa.root, pa.algo, pa.n and reads
+// only pa.bases (pa.P <= kInlineMaxRanks, else hipErrorInvalidValue).
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
-                             int last_step, hipStream_t stream);
+                             int last_step, bool from_tables, hipStream_t stream);
 
 }  // namespace vbcast

@@ -27,6 +27,9 @@ ALGO_NAMES = {v: k for k, v in ALGOS.items()}
 
 RING_STEPS = 0
 RING_CHAINS = 1
+CHAIN_AUTO = 0
+CHAIN_INLINE = 1
+CHAIN_TABLES = 2
 
 SUCCESS, ERR_ARG, ERR_ROOT, ERR_COUNT, ERR_ALIGN, ERR_HIP, ERR_NOMEM, ERR_LIMIT = range(8)
 STATIC_MAX_RANKS = 513
@@ -35,7 +38,7 @@ EXPORTS = [
     "vbcast_comm_create", "vbcast_comm_destroy", "bcast_plan", "bcast_run", "bcast_run_static", "bcast_run_steps", "bcast_run_chain_steps",
     "bcast_run_steps_timed", "bcast_run_timed", "bcast_plan_info", "bcast_plan_export", "bcast_plan_export_desc",
     "bcast_plan_export_tiles", "bcast_plan_export_chain", "bcast_plan_census", "bcast_plan_destroy", "vbcast_set_tile_bytes", "vbcast_set_chain_slab_bytes",
-    "vbcast_set_ring_executor", "vbcast_set_chain_workgroups_per_cu", "vbcast_set_xcd_count", "vbcast_select_algo",
+    "vbcast_set_ring_executor", "vbcast_set_chain_schedule", "vbcast_set_chain_workgroups_per_cu", "vbcast_set_xcd_count", "vbcast_select_algo",
     "bcast_plan_smp", "bcast_run_smp", "bcast_run_smp_phase", "bcast_smp_subplan",
     "bcast_plan_smp_destroy", "bcast_strerror",
 ]
@@ -50,6 +53,7 @@ class PlanInfo(C.Structure):
         ("scatter_bytes", C.c_uint64), ("ring_bytes", C.c_uint64),
         ("bytes_moved", C.c_uint64), ("ring_msgs_issued", C.c_uint64),
         ("pairing_mismatches", C.c_uint64), ("n_tiles", C.c_uint64),
+        ("run_launches", C.c_uint64),
     ]
 
 
@@ -107,6 +111,7 @@ def lib():
     L.vbcast_set_ring_executor.argtypes = [C.c_int]
     L.vbcast_set_chain_workgroups_per_cu.argtypes = [C.c_int]
     L.vbcast_set_xcd_count.argtypes = [C.c_int]
+    L.vbcast_set_chain_schedule.argtypes = [C.c_int]
     L.bcast_plan_smp.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int, vp, C.POINTER(vp)]
     L.bcast_run_smp.argtypes = [vp, vp]
     L.bcast_run_smp_phase.argtypes = [vp, C.c_int, vp]
@@ -158,6 +163,10 @@ def vbcast_set_ring_executor(mode: int) -> None:
 
 def vbcast_set_chain_workgroups_per_cu(k: int) -> None:
     _check(lib().vbcast_set_chain_workgroups_per_cu(k))
+
+
+def vbcast_set_chain_schedule(mode: int) -> None:
+    _check(lib().vbcast_set_chain_schedule(mode))
 
 
 def vbcast_set_xcd_count(n_xcd: int) -> None:

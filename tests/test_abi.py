@@ -75,6 +75,8 @@ def test_invalid_arguments_are_rejected_without_a_device():
     assert lib.vbcast_set_chain_slab_bytes(3000) == V.ERR_ARG
     assert lib.vbcast_set_chain_slab_bytes(8192) == V.SUCCESS
     assert lib.vbcast_set_ring_executor(7) == V.ERR_ARG
+    assert lib.vbcast_set_chain_schedule(3) == V.ERR_ARG
+    assert lib.vbcast_set_chain_schedule(V.CHAIN_AUTO) == V.SUCCESS
     assert lib.vbcast_set_chain_workgroups_per_cu(0) == V.ERR_ARG
     assert lib.bcast_run_timed(None, None, None) == V.ERR_ARG
     assert lib.bcast_plan_census(None, 24, None, None) == V.ERR_ARG

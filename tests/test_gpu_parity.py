@@ -25,14 +25,20 @@ def V():
     vbcast.vbcast_set_tile_bytes(DEFAULT_TILE)
     vbcast.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
     vbcast.vbcast_set_ring_executor(vbcast.RING_CHAINS)
+    vbcast.vbcast_set_chain_schedule(vbcast.CHAIN_AUTO)
     return vbcast
 
 
+# "chains": the one-launch executor as it comes (it works its hops out itself for
+# short broadcasts and looks them up for long ones); "inline" / "tables": the same
+# kernel held to one of the two; "steps": one launch per step over the step tables.
 EXECUTORS = ["chains", "steps"]
+ALL_EXECUTORS = ["inline", "tables", "steps"]
 
 
 def set_executor(V, name):
-    V.vbcast_set_ring_executor(V.RING_CHAINS if name == "chains" else V.RING_STEPS)
+    V.vbcast_set_ring_executor(V.RING_STEPS if name == "steps" else V.RING_CHAINS)
+    V.vbcast_set_chain_schedule({"inline": V.CHAIN_INLINE, "tables": V.CHAIN_TABLES}.get(name, V.CHAIN_AUTO))
 
 
 def sync():
@@ -165,7 +171,11 @@ def test_edge_cases_every_step(V, algo):
         check_tables(plan, sched)
         check_desc(plan, w)
         check_chain(plan, sched)
-        for ex in EXECUTORS:
+        plan.destroy()
+        for ex in ALL_EXECUTORS:
+            set_executor(V, ex)
+            plan = V.bcast_plan(comm, n, 1, root, algo)
+            set_executor(V, "chains")
             H.refill(state, w)
             ref = H.host_buffers(w, pad=40)
             for s in range(sched.n_steps):
@@ -173,10 +183,10 @@ def test_edge_cases_every_step(V, algo):
                 O.apply_step(ref, sched.steps[s])
                 got = state.cpu().numpy()
                 assert np.array_equal(got, np.stack(ref)), (P, root, n, algo, ex, s)
-        # and the graph from a fresh state, with either ring executor
+            plan.destroy()
+        # and the whole broadcast from a fresh state, every way of running it
         want = np.stack(O.broadcast_definition(H.host_buffers(w, pad=40), root, n))
-        plan.destroy()
-        for ex in EXECUTORS:
+        for ex in ALL_EXECUTORS:
             set_executor(V, ex)
             plan = V.bcast_plan(comm, n, 1, root, algo)
             set_executor(V, "chains")
@@ -190,14 +200,15 @@ def test_edge_cases_every_step(V, algo):
 
 # ------------------------------------------------------------------ the workloads
 
-@pytest.mark.parametrize("executor", EXECUTORS)
+@pytest.mark.parametrize("executor", ALL_EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("name", ["P10_n512K", "P24_n4M"])
 def test_state_after_every_step(V, name, algo, executor):
     """State of every rank buffer after every step, with the per-step kernel and
-    with the one-launch executor's kernel held to one step at a time."""
+    with the one-launch executor's kernel held to one step at a time (hops worked
+    out in the kernel, or looked up)."""
     w = I.workload(name)
-    state, comm, plan = make(V, w, algo)
+    state, comm, plan = make(V, w, algo, executor=executor)
     sched = O.build_schedule(w.P, w.root, w.n, algo)
     t = check_tables(plan, sched)
     check_desc(plan, w)
@@ -239,13 +250,13 @@ def test_state_at_sampled_steps(V, name, algo, executor):
     comm.destroy()
 
 
-@pytest.mark.parametrize("executor", EXECUTORS)
+@pytest.mark.parametrize("executor", ALL_EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("name", ["P10_n512K", "P24_n4M", "P64_n16M", "P96_n12M_ragged"])
 def test_graph_run_final_state(V, name, algo, executor):
-    """bcast_run (the graph) from a fresh state, twice; the second launch
-    regenerates the tables and must give the same result.  Both ways of running
-    the ring phase."""
+    """bcast_run from a fresh state, twice (the one kernel, or the graph, whose
+    second launch regenerates the tables and must give the same result).  Every
+    way of running the ring phase."""
     w = I.workload(name)
     state, comm, plan = make(V, w, algo, executor=executor)
     want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
@@ -646,12 +657,15 @@ def test_chunk_sizes_around_the_slab_sizes(V, P):
             state = H.device_buffers(w)
             comm = V.Comm([state[r].data_ptr() for r in range(P)], state.shape[1])
             for algo in ALGOS:
-                plan = V.bcast_plan(comm, n, 1, w.root, algo)
-                H.refill(state, w)
-                plan.run()
-                sync()
-                assert np.array_equal(state.cpu().numpy(), want), (P, n, ss, algo)
-                plan.destroy()
+                for ex in ("inline", "tables"):
+                    set_executor(V, ex)
+                    plan = V.bcast_plan(comm, n, 1, w.root, algo)
+                    set_executor(V, "chains")
+                    H.refill(state, w)
+                    plan.run()
+                    sync()
+                    assert np.array_equal(state.cpu().numpy(), want), (P, n, ss, algo, ex)
+                    plan.destroy()
             comm.destroy()
 
 
@@ -683,7 +697,7 @@ def test_random_shapes_final_state(V):
         V.vbcast_set_chain_slab_bytes(rnd.choice([4096, 8192, 16384, 65536]))
         try:
             state, comm, plan = make(V, w, algo, pad=rnd.choice([0, 1, 40, 300]),
-                                     executor=rnd.choice(EXECUTORS))
+                                     executor=rnd.choice(ALL_EXECUTORS))
         finally:
             V.vbcast_set_tile_bytes(DEFAULT_TILE)
             V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
@@ -732,10 +746,11 @@ def test_runs_on_a_side_stream_and_back_to_back(V):
     comm.destroy()
 
 
-@pytest.mark.parametrize("executor", EXECUTORS)
+@pytest.mark.parametrize("executor", ALL_EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 def test_graph_replays(V, algo, executor):
-    """The same instantiated graph launched five times, with the harness's own
+    """The same plan (its instantiated graph; for the default executor its one
+    kernel) launched five times, with the harness's own
     eager work (re-poisoning, copies back to the host) and synchronisations
     between the launches: every replay must give the state the un-graphed steps
     give, which is the oracle's."""
@@ -921,16 +936,20 @@ def expected_rows(w, sched, k, ranks, stride):
     return out
 
 
-@pytest.mark.parametrize("slab", [32768, 65536])
-def test_large_slabs_on_a_large_message(V, slab):
+@pytest.mark.parametrize("slab,hops", [(16384, "inline"), (32768, "inline"), (32768, "tables"), (65536, "chains")])
+def test_large_slabs_on_a_large_message(V, slab, hops):
     """Slabs of 32 and 64 KiB are only kept for messages with enough of them (the
     launch halves them otherwise): 16 ranks, 96 MiB + 12345 bytes, so that the
-    wavefront that has the turn copies its slab in several batches.  Sampled ranks
-    at sampled steps against the oracle's chunk-ownership form; then the graph,
-    every rank against the message."""
+    wavefront that has the turn copies its slab in several batches; with 16 KiB
+    slabs the same message has the wavefronts take turns on whole slabs and meet
+    slabs in which two chunks join.  The kernel works its hops out or looks them up
+    (as it comes, a message of this length has it look them up).  Sampled ranks at
+    sampled steps against the oracle's chunk-ownership form; then bcast_run, every
+    rank against the message."""
     import torch
     w = I.Workload(f"slab_{slab}", 16, 5, (96 << 20) + 12345, seed=4242 + slab)
     V.vbcast_set_chain_slab_bytes(slab)
+    set_executor(V, hops)
     try:
         state = H.device_buffers(w)
         stride = state.shape[1]
@@ -950,7 +969,7 @@ def test_large_slabs_on_a_large_message(V, slab):
                 sync()
                 want = expected_rows(w, sched, stop, ranks, stride)
                 for r in ranks:
-                    assert np.array_equal(state[r].cpu().numpy(), want[r]), (slab, algo, stop, r)
+                    assert np.array_equal(state[r].cpu().numpy(), want[r]), (slab, hops, algo, stop, r)
             H.refill(state, w)
             V.bcast_run(plan)
             sync()
@@ -961,6 +980,7 @@ def test_large_slabs_on_a_large_message(V, slab):
         comm.destroy()
     finally:
         V.vbcast_set_chain_slab_bytes(DEFAULT_SLAB)
+        set_executor(V, "chains")
 
 
 @pytest.mark.parametrize("algo", ALGOS)
