@@ -511,8 +511,7 @@ def main() -> int:
                         "seeded uniform random bytes; step = one tuned broadcast = one bcast_run "
                         + ("(one kernel: scatter + ring, schedule worked out in the kernel)"
                            if tuned["launches_per_bcast"] == 1 else
-                           f"(one graph launch of {tuned['launches_per_bcast']} kernels: table generation, "
-                           "then scatter + ring)"),
+                           f"({tuned['launches_per_bcast']} kernels: table generation, then scatter + ring)"),
             "tile_bytes": int(info.tile_bytes),
             "slab_bytes": args.slab_bytes or 16384,
             "ring_executor": executor,

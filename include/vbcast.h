@@ -117,8 +117,10 @@ int vbcast_comm_destroy(vbcast_comm *comm);
  * relative rank, ring neighbours and tuned switch point (step, flag), the
  * scatter-level tables [Sec. III-A, Figs. 1-2], the ring-step tables
  * [Sec. III-A Fig. 3 for NATIVE; Sec. IV Figs. 4-5 for TUNED], and for every
- * step the map from copy tiles to rows.  Then record one graph that holds the
- * table-generation kernels followed by the copy kernels.
+ * step the map from copy tiles to rows.  Where bcast_run is to go step by step
+ * (VBCAST_RING_STEPS, and the algorithms that have no other way), then record
+ * one graph that holds the table-generation kernels followed by the copy
+ * kernels.
  *   comm        communicator; must outlive the plan.  The device that was current
  *               when it was created must be current now (ARG otherwise).
  *   count, dtype_size   message = count * dtype_size bytes; 0 is valid.
@@ -137,14 +139,16 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
 /*
  * Run the whole broadcast [Sec. IV, listing: scatter, then ring] on hip_stream
  * and return without waiting (MPI's "blocking" is the caller's stream
- * synchronisation).  Where the one-launch executor works its schedule out
- * itself (VBCAST_RING_CHAINS with VBCAST_CHAIN_INLINE, which VBCAST_CHAIN_AUTO
- * picks for short broadcasts; native and tuned plans) this is a single kernel
- * launch: the kernel derives every chunk's path through the scatter tree and
- * the ring from (P, root, n, schedule) while it copies, and no table is read.
- * Otherwise it launches the plan's graph, which regenerates the tables on the
- * device, then executes the scatter levels in order and then the ring steps
- * (see vbcast_set_ring_executor and vbcast_set_chain_schedule).
+ * synchronisation).  With the one-launch executor (VBCAST_RING_CHAINS; native
+ * and tuned plans) these are plain kernel launches: one, where the kernel works
+ * its schedule out itself - it derives every chunk's path through the scatter
+ * tree and the ring from (P, root, n, schedule) while it copies, and no table is
+ * read (VBCAST_CHAIN_INLINE, which VBCAST_CHAIN_AUTO picks for all but long
+ * broadcasts) - or three, the two table kernels and then the copy kernel that
+ * looks the schedule up.  Otherwise it launches the plan's graph, which
+ * regenerates the tables on the device, then executes the scatter levels in
+ * order and then the ring steps, one kernel per step (see
+ * vbcast_set_ring_executor and vbcast_set_chain_schedule).
  * Errors: ARG (null), HIP.
  */
 int bcast_run(const vbcast_plan *plan, void *hip_stream);
@@ -249,9 +253,9 @@ typedef struct vbcast_plan_info {
     uint64_t pairing_mismatches; /* ring (step, rank) pairs where the sender's and the
                                     receiver's own decisions disagree; always 0 */
     uint64_t n_tiles;            /* copy tiles over all steps */
-    uint64_t run_launches;       /* kernel launches one bcast_run makes: 1 when the one-launch
-                                    executor works its schedule out itself, else the table
-                                    kernels plus the copy kernels of the plan's graph */
+    uint64_t run_launches;       /* kernels one bcast_run runs: 1 when the one-launch executor
+                                    works its schedule out itself, 3 when it looks it up, else
+                                    the table kernels plus one copy kernel per step (a graph) */
 } vbcast_plan_info;
 
 /* Fill *info (host pointer) from the counts read back at plan time. */
@@ -397,11 +401,11 @@ int vbcast_set_tile_bytes(size_t tile_bytes);
 int vbcast_set_chain_slab_bytes(size_t slab_bytes);
 
 /*
- * How the graphs of plans created afterwards execute the scatter levels and the
+ * How bcast_run of plans created afterwards executes the scatter levels and the
  * P-1 ring steps [Sec. III-A: a subtree root passes on part of what it received;
  * a rank forwards in ring step i+1 the chunk it received in step i]:
- *   VBCAST_RING_STEPS   one copy kernel per step, in step order; every step is
- *                       complete before the next starts.
+ *   VBCAST_RING_STEPS   one copy kernel per step, in step order, all in one graph;
+ *                       every step is complete before the next starts.
  *   VBCAST_RING_CHAINS  (default) one launch for the scatter and the ring together:
  *                       every piece of every chunk is carried down its path in the
  *                       scatter tree and then through its P-1 ring transfers, in
@@ -423,22 +427,22 @@ int vbcast_set_ring_executor(int mode);
  *                        chunk's path down the binomial tree [Sec. III-A], its P-1
  *                        ring transfers, and for the tuned schedule the step from
  *                        which the receiving rank no longer receives [Sec. IV].
- *                        No table is read; bcast_run is that one kernel launch,
- *                        without a graph.  Up to 1024 ranks (the kernel keeps the
+ *                        No table is read; bcast_run is that one kernel launch.
+ *                        Up to 1024 ranks (the kernel keeps the
  *                        hops of the chunks it is busy with in LDS); larger
  *                        communicators use VBCAST_CHAIN_TABLES whatever is set.
  *   VBCAST_CHAIN_TABLES  the kernel looks it up in the chunk-major view of the step
- *                        tables; bcast_run launches a graph of the table kernels
- *                        followed by the copy kernel.  bcast_run_static always
- *                        works this way.
- *   VBCAST_CHAIN_AUTO    (default) INLINE for short broadcasts, where the two table
- *                        kernels and the graph launch are a large part of the
- *                        time; TABLES when every resident workgroup walks 16 or
- *                        more slabs of the message, where they are not and where
- *                        the lookups - scalar loads that miss their cache and come
- *                        back after one trip to the L2 - keep a workgroup from
- *                        issuing steps faster than the L2 answers, which measures a
- *                        few per cent faster once the device is saturated.
+ *                        tables; bcast_run launches the two table kernels and then
+ *                        the copy kernel.  bcast_run_static always works this way.
+ *   VBCAST_CHAIN_AUTO    (default) INLINE, except for long broadcasts - a resident
+ *                        workgroup has 4096 or more steps to go through (its share
+ *                        of the message's slabs times the steps of the schedule) -
+ *                        which use TABLES: the two table kernels no longer count
+ *                        there, and the lookups - scalar loads that miss their
+ *                        cache and come back after one trip to the L2 - keep a
+ *                        workgroup from issuing steps faster than the L2 answers,
+ *                        which measures a few per cent faster once every compute
+ *                        unit has been streaming for a while.
  * All copy the same rows.  Process-wide; ARG for other values.
  */
 int vbcast_set_chain_schedule(int mode);

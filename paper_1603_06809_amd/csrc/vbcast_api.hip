@@ -205,8 +205,7 @@ bool one_launch(const vbcast_plan *plan) {
     return (a == VBCAST_NATIVE || a == VBCAST_TUNED) && plan->ring_executor == VBCAST_RING_CHAINS;
 }
 
-// The whole broadcast is one kernel that reads no table: bcast_run launches it
-// as it is, and the plan has no graph.
+// The whole broadcast is one kernel that reads no table.
 bool single_kernel(const vbcast_plan *plan) { return one_launch(plan) && !plan->chain_from_tables; }
 
 // The scatter levels, the way the plan's graph runs them: step by step, or not at
@@ -238,7 +237,10 @@ int graph_tile_map_steps(const vbcast_plan *plan) {
 }
 
 int build_graph(vbcast_plan *plan) {
-    if (single_kernel(plan)) return VBCAST_SUCCESS;   // nothing to chain
+    // One to three launches are cheaper made directly than through a graph (about
+    // 20 us per graph launch against 5 us per kernel launch, which overlap with the
+    // kernels already queued): the one-launch executor has no graph.
+    if (one_launch(plan)) return VBCAST_SUCCESS;
     hipStream_t cap = nullptr;
     HIP_TRY(hipStreamCreateWithFlags(&cap, hipStreamNonBlocking));
     int rc = VBCAST_SUCCESS;
@@ -248,9 +250,6 @@ int build_graph(vbcast_plan *plan) {
         return hip_fail(e, "hipStreamBeginCapture");
     }
     const PlanArrays &pa = plan->pa;
-    // The one-launch executor, when it looks its hops up, reads the chain view, not
-    // tile maps: its graph does not rebuild them (they were built at plan time for
-    // bcast_run_steps).
     e = vbcast::launch_plan_kernels(pa, graph_tile_map_steps(plan), cap);
     if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
     if (rc == VBCAST_SUCCESS) rc = launch_scatter(plan, cap);
@@ -437,11 +436,13 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     plan->ring_executor = g_ring_executor.load();
     plan->chain_grid = (uint32_t)comm->compute_units * (uint32_t)g_chain_wgs_per_cu.load();
     {
-        // AUTO: look the hops up once every resident workgroup has 16 or more slabs of
-        // the message to walk (see vbcast_set_chain_schedule), else work them out
+        // AUTO: look the hops up when a resident workgroup has 4096 or more steps to
+        // go through in the launch (its share of the slabs times the steps of a
+        // slab; see vbcast_set_chain_schedule), else work them out
         const int mode = g_chain_schedule.load();
         const uint64_t slabs = (n + (uint64_t(1) << pa.slab_log2) - 1) >> pa.slab_log2;
-        const bool long_run = slabs >= 16ull * plan->chain_grid;
+        const uint64_t share = (slabs + plan->chain_grid - 1) / plan->chain_grid;
+        const bool long_run = share * (uint64_t)pa.n_steps >= 4096;
         plan->chain_from_tables = mode == VBCAST_CHAIN_TABLES || P > vbcast::kInlineMaxRanks ||
                                   (mode == VBCAST_CHAIN_AUTO && long_run);
     }
@@ -487,7 +488,16 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
 
 int bcast_run(const vbcast_plan *plan, void *hip_stream) {
     if (!plan) return VBCAST_ERR_ARG;
-    if (single_kernel(plan)) return launch_ring(plan, static_cast<hipStream_t>(hip_stream));
+    if (one_launch(plan)) {
+        // the copy kernel alone, or behind the two table kernels whose chain view it
+        // reads (not the tile maps: those were built at plan time for bcast_run_steps)
+        hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+        if (plan->chain_from_tables) {
+            hipError_t e = vbcast::launch_plan_kernels(plan->pa, 0, stream);
+            if (e != hipSuccess) return hip_fail(e, "plan kernels");
+        }
+        return launch_ring(plan, stream);
+    }
     if (!plan->exec) return VBCAST_ERR_ARG;
     HIP_TRY(hipGraphLaunch(plan->exec, static_cast<hipStream_t>(hip_stream)));
     return VBCAST_SUCCESS;

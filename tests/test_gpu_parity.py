@@ -210,6 +210,10 @@ def test_state_after_every_step(V, name, algo, executor):
     w = I.workload(name)
     state, comm, plan = make(V, w, algo, executor=executor)
     sched = O.build_schedule(w.P, w.root, w.n, algo)
+    # kernels per bcast_run: the copy kernel alone; behind the two table kernels; or
+    # three table kernels and one copy kernel per step that moves something
+    assert plan.info().run_launches == {"inline": 1, "tables": 3}.get(
+        executor, 3 + sum(1 for rows in sched.steps if rows))
     t = check_tables(plan, sched)
     check_desc(plan, w)
     check_chain(plan, sched)
@@ -993,6 +997,8 @@ def test_large_workload_state(V, big, algo):
     stride = state.shape[1]
     comm = V.Comm([state[r].data_ptr() for r in range(w.P)], stride)
     plan = V.bcast_plan(comm, w.n, 1, w.root, algo)
+    # a broadcast this long looks its hops up: two table kernels, then the copy kernel
+    assert plan.info().run_launches == 3
     sched = O.build_schedule(w.P, w.root, w.n, algo)
     nsc, S = sched.n_scatter_steps, sched.n_steps
     ranks = [w.root, (w.root + 1) % w.P, (w.root + 256) % w.P, (w.root + 384) % w.P,
