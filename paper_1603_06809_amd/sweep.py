@@ -2,7 +2,7 @@
 experiments [Sec. V]: long messages on 16, 64 and 256 processes; 12288,
 524287 and 1048576 bytes on 9, 17, 33, 65 and 129 processes; 12288 to 2560000
 bytes on 129 processes.  For every point the native and the tuned broadcast
-are timed as graph launches on one GPU and set side by side.
+are timed as bcast_run calls on one GPU and set side by side.
 
     python -m paper_1603_06809_amd.sweep [--iters 100] [--markdown]
     python -m paper_1603_06809_amd.sweep --selection [--markdown]
@@ -27,7 +27,7 @@ to cross the HBM interface over the time; small workloads that fit the 256 MB
 Infinity Cache may not reach HBM at all, so for them this is an upper bound of
 the traffic, not a measurement).  The paper's
 protocol is a barrier followed by 100 iterations; here that is a stream
-synchronisation followed by ``--iters`` graph launches.
+synchronisation followed by ``--iters`` bcast_run calls.
 """
 
 from __future__ import annotations
