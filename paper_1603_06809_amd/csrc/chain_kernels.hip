@@ -47,6 +47,7 @@ namespace vbcast {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr uint32_t kLine = 128;    // bytes of a cache line
 constexpr int kMinSlabLog2 = 10;   // smallest slab: one wavefront, one word per lane
 constexpr int kFillSlabLog2 = 12;  // slabs are not made smaller than this just to get more of them
 
@@ -244,6 +245,62 @@ __device__ __forceinline__ const uint8_t *buffer_of(uint64_t entry) {
     return reinterpret_cast<const uint8_t *>(entry & ~15ull);
 }
 
+// The cache line in which chunks c - 1 and c meet (none when chunk c starts on a
+// line boundary, or is empty): bytes below the cut follow chunk c - 1's chain,
+// bytes from the cut on chunk c's, one lane per byte, through steps [first_step,
+// last_step).  Every buffer gets this line in two parts, in different steps, and
+// a step on a partly written line costs about twice a step on whole lines; as a
+// chain of its own - one workgroup per line, beside the workgroups that walk the
+// slabs - it is 128 bytes that take a few hundred microseconds at most and hold
+// nothing else up.  Called by all threads of the workgroup.
+template <int THREADS, class Hops>
+__device__ __forceinline__ void walk_cut_line(Hops &hops, uint64_t *lds, int c, uint64_t n,
+                                              uint32_t first_step, uint32_t last_step) {
+    const uint64_t cut = hops.chunk_begin(c);
+    if (cut >= n || (cut & (kLine - 1)) == 0) return;   // the same for the whole workgroup
+    hops.prepare(lds, c - 1, c, first_step, last_step);
+    const uint64_t line = cut & ~(uint64_t)(kLine - 1);
+    constexpr int PER_LANE = THREADS >= (int)kLine ? 1 : (int)kLine / THREADS;
+    uint64_t at[PER_LANE];
+    bool in_a[PER_LANE], in_b[PER_LANE];
+#pragma unroll
+    for (int k = 0; k < PER_LANE; ++k) {
+        const uint32_t b = threadIdx.x + (uint32_t)k * THREADS;
+        at[k] = line + b;
+        const bool in_line = b < kLine && at[k] < n;
+        in_a[k] = in_line && at[k] < cut;
+        in_b[k] = in_line && at[k] >= cut;
+    }
+    const uint8_t *srcA = buffer_of(hops.source(c - 1, first_step));
+    const uint8_t *srcB = buffer_of(hops.source(c, first_step));
+    uint64_t eA = hops.entry(c - 1, first_step);
+    uint64_t eB = hops.entry(c, first_step);
+    for (uint32_t i = first_step + 1; i <= last_step; ++i) {
+        const uint32_t nx = i < last_step ? i : first_step;
+        const uint64_t nA = hops.entry(c - 1, nx);
+        const uint64_t nB = hops.entry(c, nx);
+        uint8_t *dA = reinterpret_cast<uint8_t *>(eA & ~15ull);
+        uint8_t *dB = reinterpret_cast<uint8_t *>(eB & ~15ull);
+        const bool runA = !(eA & 1), runB = !(eB & 1);
+        uint8_t one[PER_LANE];
+        bool on[PER_LANE];
+#pragma unroll
+        for (int k = 0; k < PER_LANE; ++k) {
+            on[k] = (in_a[k] && runA) || (in_b[k] && runB);
+            if (on[k]) one[k] = *gmem_bytes((in_a[k] ? srcA : srcB) + at[k]);
+        }
+        wait_for_loads();
+#pragma unroll
+        for (int k = 0; k < PER_LANE; ++k)
+            if (on[k]) *gmem_bytes((in_a[k] ? dA : dB) + at[k]) = one[k];
+        step_fence();
+        srcA = dA;
+        srcB = dB;
+        eA = nA;
+        eB = nB;
+    }
+}
+
 // Steps [first_step, last_step) of every slab of the message.  `chain` and
 // `chunk_off` are read only by TableHops, `tuned` only by InlineHops.  The
 // pointers are separate restrict-qualified kernel arguments on purpose: that is
@@ -255,18 +312,24 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                                                        uint8_t *const *__restrict__ bases, int P,
                                                        int L, int root, int tuned, uint64_t n,
                                                        uint64_t ss, uint32_t n_slabs,
+                                                       uint32_t slab_wgs, uint32_t cut_wgs,
                                                        uint32_t xcd_run, uint32_t n_xcd,
                                                        uint32_t first_step, uint32_t last_step) {
     __shared__ uint64_t hop_slots[Hops::lds_words(2)];
     Hops hops = Hops::make(chain, chunk_off, bases, P, L, root, tuned, n, ss);
     hops.begin(hop_slots);
+    if (blockIdx.x >= slab_wgs) {
+        // the `cut_wgs` workgroups after those that walk slabs: one line each
+        walk_cut_line<THREADS>(hops, hop_slots, (int)(blockIdx.x - slab_wgs) + 1, n, first_step, last_step);
+        return;
+    }
     const uint32_t scatter_hops = (uint32_t)L;
     constexpr uint64_t TILE = 1ull << TILE_LOG2;
     // Workgroups are handed to the XCDs round-robin (workgroup id mod n_xcd).
     // Give each XCD runs of `xcd_run` consecutive slabs (64 KiB) instead of every
     // n-th slab, so that the addresses one XCD touches spread over all of its L2
     // channels, while the XCDs together still sweep one contiguous window.
-    const uint32_t W = gridDim.x;  // a multiple of n_xcd; W / n_xcd is a multiple of xcd_run
+    const uint32_t W = slab_wgs;  // a multiple of n_xcd; W / n_xcd is a multiple of xcd_run
     const uint32_t in_xcd = blockIdx.x / n_xcd;
     const uint32_t first = (in_xcd / xcd_run) * n_xcd * xcd_run + (blockIdx.x % n_xcd) * xcd_run +
                            (in_xcd % xcd_run);
@@ -391,15 +454,22 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
                 e = nxt;
             }
         } else {
-            // One or two chunks meet in this slab (or the message ends in it).  The
-            // slab is still a row of 16-byte words at fixed places: a lane keeps its
-            // PER_LANE words and only picks, per word, which of the two chains the
-            // word belongs to.  The word that holds the cut between the chunks and
-            // the word that holds the end of the message go byte by byte, one lane
-            // per byte (lanes 0-15 and 16-31).
+            // Two chunks meet in this slab (or the message ends in it).  The slab is
+            // still a row of 16-byte words at fixed places: a lane keeps its PER_LANE
+            // words and only picks, per word, which of the two chains the word belongs
+            // to.  The word that holds the cut between the chunks and the word that
+            // holds the end of the message go byte by byte, one lane per byte (lanes
+            // 0-15 and 16-31).  With `cut_wgs` the cache line in which the two chunks
+            // meet is left out here and walked by a workgroup of its own
+            // (walk_cut_line): every buffer gets that line in two parts, in different
+            // steps, a line that is only partly written is not re-read from the L1, and
+            // walked with the slab it makes every step of the whole slab wait for it.
             constexpr int PER_LANE = (int)(TILE / 16) / THREADS;
             const uint32_t tid = threadIdx.x;
-            const uint64_t cut = c1 > c0 ? hops.chunk_begin(c1) : hi;   // A = [lo, cut), B = [cut, hi)
+            const uint64_t cut = c1 > c0 ? hops.chunk_begin(c1) : hi;
+            const bool apart = c1 > c0 && cut_wgs != 0;
+            const uint64_t a_end = apart ? cut & ~(uint64_t)(kLine - 1) : cut;                  // A = [lo, a_end)
+            const uint64_t b_begin = apart ? (cut + kLine - 1) & ~(uint64_t)(kLine - 1) : cut;  // B = [b_begin, hi)
             const uint8_t *srcA = buffer_of(hops.source(c0, first_step));
             const uint8_t *srcB = buffer_of(hops.source(c1, first_step));
 
@@ -408,14 +478,17 @@ __global__ __launch_bounds__(THREADS) void ring_chain(const uint64_t *__restrict
 #pragma unroll
             for (int k = 0; k < PER_LANE; ++k) {
                 word_at[k] = lo + (uint64_t)(tid + k * THREADS) * 16u;
-                word_a[k] = word_at[k] + 16 <= cut;
-                word_b[k] = word_at[k] >= cut && word_at[k] + 16 <= hi;
+                word_a[k] = word_at[k] + 16 <= a_end;
+                word_b[k] = word_at[k] >= b_begin && word_at[k] + 16 <= hi;
             }
-            // byte lanes: lanes 0-15 take the word holding `cut`, 16-31 the word holding `hi`
+            // byte lanes: lanes 0-15 take the word holding `cut` (unless its line is left
+            // out), 16-31 the word holding `hi` (unless it is the same word, or left out)
             const uint64_t byte_at = (tid < 16 ? (cut & ~15ull) : (hi & ~15ull)) + (tid & 15u);
-            const bool byte_lane = tid < 32 && byte_at >= lo && byte_at < hi &&
-                                   (tid < 16 ? (cut & 15u) != 0
-                                             : ((hi & 15u) != 0 && (hi & ~15ull) != (cut & ~15ull)));
+            const bool byte_lane =
+                tid < 32 && byte_at >= lo && byte_at < hi &&
+                (tid < 16 ? (!apart && (cut & 15u) != 0)
+                          : ((hi & 15u) != 0 &&
+                             (apart ? (hi & ~15ull) >= b_begin : (hi & ~15ull) != (cut & ~15ull))));
             const bool byte_a = byte_lane && byte_at < cut;
             const bool byte_b = byte_lane && byte_at >= cut;
 
@@ -558,12 +631,26 @@ hipError_t launch_with(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int firs
     // slabs per XCD run: 64 KiB worth, but a divisor of the workgroups per XCD
     uint32_t xcd_run = tl < 16 ? (1u << (16 - tl)) : 1u;
     while ((grid / n_xcd) % xcd_run != 0) xcd_run >>= 1;
-    const dim3 g(grid);
+    // Behind the workgroups that walk slabs, one per chunk boundary for the cache line
+    // the boundary falls in (it leaves at once where the boundary falls between two
+    // lines).  A compute unit's L1 serves one dependent step at a time whichever
+    // workgroup issued it, so the line's steps add to the time of the slab walker it
+    // shares the unit with: worth it against the slab steps they no longer slow down
+    // as long as every unit gets at most one line (measured: P = 256, 30 MB 1.73 ->
+    // 1.63 ms; P = 129, 2.5 MB 90 -> 80 us; but P = 513, 32 MiB 3.64 -> 3.72 ms with
+    // 512 of them), and for slabs of 4 KiB and more (in a smaller slab the line is a
+    // large part of the slab anyway: P = 129, 192 KiB, 1 KiB slabs: 42 us with the
+    // slabs, 68 us apart).
+    const uint32_t cut_wgs =
+        tl >= kFillSlabLog2 && pa.ss % kLine != 0 && (uint32_t)pa.P - 1u <= wgs_at_plan_tile
+            ? (uint32_t)pa.P - 1u
+            : 0u;
+    const dim3 g(grid + cut_wgs);
     // one 16-byte word per lane in the two smallest slabs, so fewer lanes there
 #define VB_LAUNCH(TL, LANES)                                                                 \
     hipLaunchKernelGGL((ring_chain<TL, LANES, Hops>), g, dim3(LANES), 0, stream, pa.chain,   \
                        pa.chunk_off, pa.bases, pa.P, pa.L, pa.root, tuned, pa.n, pa.ss, n_slabs,  \
-                       xcd_run, n_xcd, s0, s1)
+                       grid, cut_wgs, xcd_run, n_xcd, s0, s1)
     switch (tl) {
         case 10: VB_LAUNCH(10, 64); break;
         case 11: VB_LAUNCH(11, 128); break;
