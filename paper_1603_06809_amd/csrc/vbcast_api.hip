@@ -208,8 +208,8 @@ bool one_launch(const vbcast_plan *plan) {
 // The whole broadcast is one kernel that reads no table.
 bool single_kernel(const vbcast_plan *plan) { return one_launch(plan) && !plan->chain_from_tables; }
 
-// The scatter levels, the way the plan's graph runs them: step by step, or not at
-// all when the one-launch executor carries them together with the ring.
+// The scatter levels, the way bcast_run runs them: step by step, or not at all
+// when the one-launch executor carries them together with the ring.
 int launch_scatter(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0 || one_launch(plan)) return VBCAST_SUCCESS;
@@ -217,7 +217,7 @@ int launch_scatter(const vbcast_plan *plan, hipStream_t stream) {
 }
 
 // The steps after the scatter (with the one-launch executor: all steps), the way
-// the plan's graph runs them.
+// bcast_run runs them.
 int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return VBCAST_SUCCESS;
@@ -230,10 +230,25 @@ int launch_ring(const vbcast_plan *plan, hipStream_t stream) {
     return launch_steps(plan, pa.n_scatter, pa.n_steps, stream, nullptr);
 }
 
-int graph_tile_map_steps(const vbcast_plan *plan) {
+// Steps whose tile maps a broadcast rebuilds: all of them for the per-step executor;
+// none for the one-launch executor, which reads the chain view if anything (the tile
+// maps were built at plan time and serve bcast_run_steps).
+int tile_map_steps(const vbcast_plan *plan) {
     const PlanArrays &pa = plan->pa;
     if (pa.n_steps == 0) return 0;
     return one_launch(plan) ? 0 : pa.n_steps;
+}
+
+// Everything one broadcast enqueues, in order: the table kernels (unless the copy
+// kernel works the schedule out itself), the scatter levels, the ring phase.
+int enqueue_broadcast(const vbcast_plan *plan, hipStream_t stream) {
+    if (!single_kernel(plan)) {
+        hipError_t e = vbcast::launch_plan_kernels(plan->pa, tile_map_steps(plan), stream);
+        if (e != hipSuccess) return hip_fail(e, "plan kernels");
+    }
+    int rc = launch_scatter(plan, stream);
+    if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, stream);
+    return rc;
 }
 
 int build_graph(vbcast_plan *plan) {
@@ -243,17 +258,12 @@ int build_graph(vbcast_plan *plan) {
     if (one_launch(plan)) return VBCAST_SUCCESS;
     hipStream_t cap = nullptr;
     HIP_TRY(hipStreamCreateWithFlags(&cap, hipStreamNonBlocking));
-    int rc = VBCAST_SUCCESS;
     hipError_t e = hipStreamBeginCapture(cap, hipStreamCaptureModeRelaxed);
     if (e != hipSuccess) {
         (void)hipStreamDestroy(cap);
         return hip_fail(e, "hipStreamBeginCapture");
     }
-    const PlanArrays &pa = plan->pa;
-    e = vbcast::launch_plan_kernels(pa, graph_tile_map_steps(plan), cap);
-    if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
-    if (rc == VBCAST_SUCCESS) rc = launch_scatter(plan, cap);
-    if (rc == VBCAST_SUCCESS) rc = launch_ring(plan, cap);
+    const int rc = enqueue_broadcast(plan, cap);
     hipGraph_t graph = nullptr;
     e = hipStreamEndCapture(cap, &graph);
     (void)hipStreamDestroy(cap);
@@ -488,16 +498,8 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
 
 int bcast_run(const vbcast_plan *plan, void *hip_stream) {
     if (!plan) return VBCAST_ERR_ARG;
-    if (one_launch(plan)) {
-        // the copy kernel alone, or behind the two table kernels whose chain view it
-        // reads (not the tile maps: those were built at plan time for bcast_run_steps)
-        hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-        if (plan->chain_from_tables) {
-            hipError_t e = vbcast::launch_plan_kernels(plan->pa, 0, stream);
-            if (e != hipSuccess) return hip_fail(e, "plan kernels");
-        }
-        return launch_ring(plan, stream);
-    }
+    // the copy kernel alone, or behind the two table kernels whose chain view it reads
+    if (one_launch(plan)) return enqueue_broadcast(plan, static_cast<hipStream_t>(hip_stream));
     if (!plan->exec) return VBCAST_ERR_ARG;
     HIP_TRY(hipGraphLaunch(plan->exec, static_cast<hipStream_t>(hip_stream)));
     return VBCAST_SUCCESS;
@@ -614,7 +616,7 @@ int bcast_run_timed(const vbcast_plan *plan, void *hip_stream, float *phase_ms) 
     };
     mark(0);
     if (rc == VBCAST_SUCCESS && !single_kernel(plan)) {
-        hipError_t e = vbcast::launch_plan_kernels(plan->pa, graph_tile_map_steps(plan), stream);
+        hipError_t e = vbcast::launch_plan_kernels(plan->pa, tile_map_steps(plan), stream);
         if (e != hipSuccess) rc = hip_fail(e, "plan kernels");
     }
     mark(1);
@@ -849,13 +851,7 @@ int bcast_plan_smp(const vbcast_comm *comm, size_t count, size_t dtype_size, int
             if (e != hipSuccess) rc = hip_fail(e, "hipStreamBeginCapture");
             if (rc == VBCAST_SUCCESS) {
                 for (auto &sub : sp->subs) {
-                    const vbcast_plan *p = sub.plan;
-                    if (!single_kernel(p)) {
-                        e = vbcast::launch_plan_kernels(p->pa, graph_tile_map_steps(p), cap);
-                        if (e != hipSuccess) rc = hip_fail(e, "capture: plan kernels");
-                    }
-                    if (rc == VBCAST_SUCCESS) rc = launch_scatter(p, cap);
-                    if (rc == VBCAST_SUCCESS) rc = launch_ring(p, cap);
+                    rc = enqueue_broadcast(sub.plan, cap);
                     if (rc != VBCAST_SUCCESS) break;
                 }
                 hipGraph_t graph = nullptr;
