@@ -434,9 +434,10 @@ int vbcast_set_ring_executor(int mode);
  *   VBCAST_CHAIN_TABLES  the kernel looks it up in the chunk-major view of the step
  *                        tables; bcast_run launches the two table kernels and then
  *                        the copy kernel.  bcast_run_static always works this way.
- *   VBCAST_CHAIN_AUTO    (default) INLINE, except for long broadcasts - a resident
- *                        workgroup has 4096 or more steps to go through (its share
- *                        of the message's slabs times the steps of the schedule) -
+ *   VBCAST_CHAIN_AUTO    (default) INLINE, except for long broadcasts - slabs of
+ *                        16 KiB or more, and a resident workgroup has 4096 or more
+ *                        steps to go through (its share of the message's slabs
+ *                        times the steps of the schedule) -
  *                        which use TABLES: the two table kernels no longer count
  *                        there, and the lookups - scalar loads that miss their
  *                        cache and come back after one trip to the L2 - keep a

@@ -590,30 +590,8 @@ hipError_t launch_with(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int firs
     if (first_step < 0 || last_step > pa.n_steps) return hipErrorInvalidValue;
     const uint32_t s0 = (uint32_t)first_step, s1 = (uint32_t)last_step;
     const int tuned = pa.algo == kAlgoTuned ? 1 : 0;
-    // Slab size: the plan's slab size, halved (with twice the workgroups, so the
-    // bytes in flight stay the same)
-    //  - while a slab is longer than a chunk: it must not hold more than one chunk
-    //    boundary (down to 1 KiB);
-    //  - down to 4 KiB, while chunks are not a whole number of slabs and hold fewer
-    //    than four: slabs in which two chunks meet cost more per step (partly
-    //    written lines, single bytes), so they should be few and small;
-    //  - down to 8 KiB, while the workgroups would get fewer than four slabs each,
-    //    and down to 4 KiB, while there are fewer slabs than workgroups: a medium
-    //    message is then spread over more compute units, each step of its chains
-    //    moving less per workgroup.
-    int tl = pa.slab_log2;
-    uint64_t grid64 = wgs_at_plan_tile;
-    while (tl > kMinSlabLog2) {
-        const uint64_t slab = 1ull << tl;
-        const uint64_t n_slabs = (pa.n + slab - 1) >> tl;
-        const bool too_long = slab > pa.ss;
-        const bool many_cuts = tl > kFillSlabLog2 && pa.ss % slab != 0 && slab * 4 > pa.ss;
-        const bool too_few = (tl > kFillSlabLog2 + 1 && n_slabs < 4 * grid64) ||
-                             (tl > kFillSlabLog2 && n_slabs < grid64);
-        if (!too_long && !many_cuts && !too_few) break;
-        --tl;
-        grid64 *= 2;
-    }
+    uint64_t grid64 = 0;
+    const int tl = chain_slab_log2(pa, wgs_at_plan_tile, &grid64);
     if ((1ull << tl) > pa.ss) {
         // chunks shorter than 1 KiB: one wavefront per chunk
         const uint32_t per_wg = kThreads / 64;
@@ -666,6 +644,35 @@ hipError_t launch_with(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int firs
 }
 
 }  // namespace
+
+int chain_slab_log2(const PlanArrays &pa, uint32_t wgs_at_plan_tile, uint64_t *workgroups) {
+    // The plan's slab size, halved (with twice the workgroups, so the bytes in flight
+    // stay the same)
+    //  - while a slab is longer than a chunk: it must not hold more than one chunk
+    //    boundary (down to 1 KiB);
+    //  - down to 4 KiB, while chunks are not a whole number of slabs and hold fewer
+    //    than four: slabs in which two chunks meet cost more per step (partly
+    //    written lines, single bytes), so they should be few and small;
+    //  - down to 8 KiB, while the workgroups would get fewer than four slabs each,
+    //    and down to 4 KiB, while there are fewer slabs than workgroups: a medium
+    //    message is then spread over more compute units, each step of its chains
+    //    moving less per workgroup.
+    int tl = pa.slab_log2;
+    uint64_t grid64 = wgs_at_plan_tile;
+    while (tl > kMinSlabLog2) {
+        const uint64_t slab = 1ull << tl;
+        const uint64_t n_slabs = (pa.n + slab - 1) >> tl;
+        const bool too_long = slab > pa.ss;
+        const bool many_cuts = tl > kFillSlabLog2 && pa.ss % slab != 0 && slab * 4 > pa.ss;
+        const bool too_few = (tl > kFillSlabLog2 + 1 && n_slabs < 4 * grid64) ||
+                             (tl > kFillSlabLog2 && n_slabs < grid64);
+        if (!too_long && !many_cuts && !too_few) break;
+        --tl;
+        grid64 *= 2;
+    }
+    if (workgroups) *workgroups = grid64;
+    return tl;
+}
 
 hipError_t launch_ring_chain(const PlanArrays &pa, uint32_t wgs_at_plan_tile, int first_step,
                              int last_step, bool from_tables, hipStream_t stream) {

@@ -446,13 +446,16 @@ int bcast_plan(const vbcast_comm *comm, size_t count, size_t dtype_size, int roo
     plan->ring_executor = g_ring_executor.load();
     plan->chain_grid = (uint32_t)comm->compute_units * (uint32_t)g_chain_wgs_per_cu.load();
     {
-        // AUTO: look the hops up when a resident workgroup has 4096 or more steps to
-        // go through in the launch (its share of the slabs times the steps of a
-        // slab; see vbcast_set_chain_schedule), else work them out
+        // AUTO: look the hops up when the launch walks slabs of 16 KiB or more (the
+        // wavefronts of a workgroup then take turns, and the lookups pace them) and a
+        // workgroup has 4096 or more steps to go through (its share of the slabs times
+        // the steps of a slab; see vbcast_set_chain_schedule), else work them out
         const int mode = g_chain_schedule.load();
-        const uint64_t slabs = (n + (uint64_t(1) << pa.slab_log2) - 1) >> pa.slab_log2;
-        const uint64_t share = (slabs + plan->chain_grid - 1) / plan->chain_grid;
-        const bool long_run = share * (uint64_t)pa.n_steps >= 4096;
+        uint64_t wgs = 0;
+        const int tl = vbcast::chain_slab_log2(pa, plan->chain_grid, &wgs);
+        const uint64_t slabs = (n + (uint64_t(1) << tl) - 1) >> tl;
+        const uint64_t share = wgs ? (slabs + wgs - 1) / wgs : 0;
+        const bool long_run = tl >= 14 && share * (uint64_t)pa.n_steps >= 4096;
         plan->chain_from_tables = mode == VBCAST_CHAIN_TABLES || P > vbcast::kInlineMaxRanks ||
                                   (mode == VBCAST_CHAIN_AUTO && long_run);
     }

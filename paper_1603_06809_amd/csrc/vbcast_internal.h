@@ -100,6 +100,12 @@ hipError_t launch_step_copy(const Row *rows, const Tile *tiles, uint8_t *const *
 constexpr int kInlineMaxRanks = 1024;
 constexpr int kInlineMaxHops = 1040;   // >= 10 + 1023
 
+// The slab size (log2 of bytes, 10..16) launch_ring_chain walks the message in, given
+// pa.n, pa.ss and pa.slab_log2, and through *workgroups (may be null) how many
+// workgroups share the slabs at that size when `wgs_at_plan_tile` would at the plan's.
+// A result above log2(pa.ss) means: chunks shorter than 1 KiB, one wavefront per chunk.
+int chain_slab_log2(const PlanArrays &pa, uint32_t wgs_at_plan_tile, uint64_t *workgroups);
+
 // Enqueue steps [first_step, last_step) of a scatter + ring broadcast (native or
 // tuned) as one launch that walks every slab of the message through those steps
 // (all of them: 0 and pa.n_steps).  `wgs_at_plan_tile` persistent workgroups
