@@ -750,6 +750,33 @@ def test_runs_on_a_side_stream_and_back_to_back(V):
     comm.destroy()
 
 
+@pytest.mark.parametrize("executor", ["inline", "tables"])
+def test_bcast_run_captured_into_a_callers_graph(V, executor):
+    """The one-launch executor's bcast_run is one or three plain kernel launches, so
+    a caller can capture it into a graph of their own (nothing in it allocates,
+    synchronises or sets memory).  Three replays with the harness's eager work
+    (re-poisoning, copies to the host, synchronisations) between them, each checked."""
+    import torch
+    w = I.workload("P24_n4M")
+    state, comm, plan = make(V, w, O.TUNED, executor=executor)
+    want = np.stack(O.broadcast_definition(H.host_buffers(w), w.root, w.n))
+    V.bcast_run(plan)           # once outside, so that nothing is set up lazily under capture
+    sync()
+    assert np.array_equal(state.cpu().numpy(), want)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        V.bcast_run(plan)       # on the capturing stream (torch's current stream here)
+    for replay in range(3):
+        H.refill(state, w)
+        sync()
+        graph.replay()
+        sync()
+        assert np.array_equal(state.cpu().numpy(), want), (executor, replay)
+    del graph
+    plan.destroy()
+    comm.destroy()
+
+
 @pytest.mark.parametrize("executor", ALL_EXECUTORS)
 @pytest.mark.parametrize("algo", ALGOS)
 def test_graph_replays(V, algo, executor):
