@@ -35,6 +35,11 @@
  * "copy length bytes at that offset from src's buffer to the same offset in
  * dst's buffer".  Rows with length 0 are not stored.  All rows of a step are
  * independent; steps must run in order.  Tables are generated on the GPU.
+ * The default executor of the two scatter + ring schedules copies the same rows
+ * without going step by step: one kernel carries every piece of every chunk
+ * through its transfers in the order they depend on each other, and for all but
+ * long broadcasts it derives those rows itself instead of reading the tables
+ * (vbcast_set_ring_executor, vbcast_set_chain_schedule).
  *
  * Conventions
  *   - All functions return 0 (VBCAST_SUCCESS) or a VBCAST_ERR_* code; nothing
