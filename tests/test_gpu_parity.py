@@ -673,6 +673,31 @@ def test_chunk_sizes_around_the_slab_sizes(V, P):
             comm.destroy()
 
 
+@pytest.mark.parametrize("P", [257, 258])
+def test_chunk_boundary_lines_around_the_rank_limit(V, P):
+    """Up to 257 ranks on a 256-unit device the one-launch executor walks the cache
+    line in which two chunks meet in a workgroup of its own, beyond that with the
+    slab it lies in: both sides of the limit, chunks of 5000 bytes (every boundary
+    inside a line), the broadcast in three pieces cut at steps 7 and n_steps - 3,
+    hops worked out and looked up, both schedules."""
+    n = P * 5000 - 7
+    w = I.Workload(f"cutline_P{P}", P, 11, n, seed=31_000 + P)
+    for algo in ALGOS:
+        sched = O.build_schedule(P, w.root, n, algo)
+        assert sched.ss == 5000
+        for ex in ("inline", "tables"):
+            state, comm, plan = make(V, w, algo, pad=24, executor=ex)
+            ref = [H.host_row(w, r, state.shape[1]) for r in range(P)]
+            for (first, last) in ((0, 7), (7, sched.n_steps - 3), (sched.n_steps - 3, sched.n_steps)):
+                plan.run_chain_steps(first, last)
+                O.run_steps(ref, sched, first, last)
+                assert np.array_equal(state.cpu().numpy(), np.stack(ref)), (P, algo, ex, first, last)
+            want = np.stack(O.broadcast_definition([H.host_row(w, r, state.shape[1]) for r in range(P)], w.root, n))
+            assert np.array_equal(np.stack(ref), want)
+            plan.destroy()
+            comm.destroy()
+
+
 def test_sweep_modes_run_and_check_their_results(V, capsys):
     """The two side sweeps (every algorithm around the size thresholds; flat
     against three-phase) return 0 only if every broadcast they timed left every
